@@ -1,0 +1,180 @@
+"""ctypes front for the C oracle (TEST INFRASTRUCTURE ONLY -- never imported by the
+product package).  All method arithmetic lives in drf_oracle.c; this file only
+marshals numpy arrays."""
+import ctypes as C
+import os
+
+import numpy as np
+
+from . import build as _build
+
+ROW = 5
+
+
+class Sched(C.Structure):
+    _fields_ = [("train_steps", C.c_int), ("beta_start", C.c_double), ("beta_end", C.c_double),
+                ("steps", C.c_int)]
+
+
+class DitConfig(C.Structure):
+    _fields_ = [(k, C.c_int) for k in ("depth", "hidden", "heads", "mlp_ratio", "patch", "in_ch",
+                                         "lat_h", "lat_w", "cond_kind", "cond_dim", "ctx_len",
+                                         "round_bf16")]
+
+
+def _ptr(a):
+    return a.ctypes.data_as(C.c_void_p) if a is not None else None
+
+
+class Oracle:
+    """bits=64: double arithmetic (authority). bits=32: float build of the same source."""
+
+    def __init__(self, bits=64):
+        _build.build()
+        self.lib = C.CDLL(_build.lib_path(bits))
+        self.real = np.float64 if bits == 64 else np.float32
+        assert self.lib.orc_real_bytes() == bits // 8
+        L = self.lib
+        L.orc_weight_count.restype = C.c_size_t
+        L.orc_abar_at.restype = C.c_double
+        L.orc_skip.argtypes = [C.c_void_p, C.c_void_p, C.c_double, C.c_double, C.c_size_t, C.c_void_p]
+        self.EPS_FN = C.CFUNCTYPE(None, C.c_void_p, C.c_void_p, C.c_int, C.c_int, C.c_void_p)
+        L.orc_sample.argtypes = [C.c_void_p, C.c_int, C.c_int, C.c_int, C.c_size_t, C.c_void_p,
+                                 C.c_void_p, C.c_void_p, C.c_void_p, C.c_void_p, C.c_size_t, C.c_void_p]
+        L.orc_dit_eps.argtypes = [C.c_void_p] * 5 + [C.c_int, C.c_void_p, C.c_int, C.c_void_p]
+        L.orc_sample_dit.argtypes = [C.c_void_p, C.c_void_p, C.c_void_p, C.c_int, C.c_int, C.c_int,
+                                     C.c_void_p, C.c_void_p, C.c_void_p, C.c_double, C.c_void_p]
+        L.orc_eps_guided.argtypes = [C.c_void_p, C.c_void_p, C.c_void_p, C.c_int, C.c_void_p,
+                                     C.c_void_p, C.c_double, C.c_int, C.c_void_p]
+
+    def threads(self):
+        return int(self.lib.orc_num_threads())
+
+    # ---- schedule
+    @staticmethod
+    def sched(d):
+        return Sched(d["train_steps"], d["beta_start"], d["beta_end"], d["steps"])
+
+    def alpha_bar(self, sd):
+        sc = self.sched(sd)
+        out = np.empty(sd["train_steps"], np.float64)
+        self.lib.orc_alpha_bar(C.byref(sc), _ptr(out))
+        return out
+
+    def tau(self, sd, s):
+        sc = self.sched(sd)
+        return int(self.lib.orc_tau(C.byref(sc), C.c_int(s)))
+
+    def abar_at(self, sd, s):
+        ab = self.alpha_bar(sd)
+        sc = self.sched(sd)
+        return float(self.lib.orc_abar_at(C.byref(sc), _ptr(ab), C.c_int(s)))
+
+    # ---- operator
+    def skip(self, x, eps, a_from, a_to):
+        x = np.ascontiguousarray(x, self.real)
+        eps = np.ascontiguousarray(eps, self.real)
+        out = np.empty_like(x)
+        self.lib.orc_skip(_ptr(x), _ptr(eps), a_from, a_to, x.size, _ptr(out))
+        return out
+
+    # ---- scheduler
+    def plan(self, sd, mode, n):
+        sc = self.sched(sd)
+        cnt = C.c_size_t(0)
+        rc = self.lib.orc_sample(C.byref(sc), mode, n, 0, 0, None, None, None, None, None, 0, C.byref(cnt))
+        if rc != 0:
+            raise ValueError("oracle rejected plan arguments")
+        rows = np.zeros((cnt.value, ROW), np.int32)
+        self.lib.orc_sample(C.byref(sc), mode, n, 0, 0, None, None, None, None, _ptr(rows), cnt.value,
+                            C.byref(cnt))
+        return rows
+
+    def sample_with(self, sd, mode, n, xT, eps_py):
+        """Run the scheduler with a Python noise predictor eps_py(x, s, tau) -> eps,
+        x shaped like xT ([batch, ...])."""
+        xT = np.ascontiguousarray(xT, self.real)
+        batch = xT.shape[0]
+        E = xT.size // batch
+        shape = xT.shape
+        real = self.real
+
+        def cb(user, xp, s, tau, outp):
+            x = np.frombuffer((C.c_char * xT.nbytes).from_address(xp), dtype=real).reshape(shape)
+            out = np.frombuffer((C.c_char * xT.nbytes).from_address(outp), dtype=real).reshape(shape)
+            out[...] = eps_py(x.copy(), s, tau)
+
+        fn = self.EPS_FN(cb)
+        x0 = np.empty_like(xT)
+        sc = self.sched(sd)
+        rc = self.lib.orc_sample(C.byref(sc), mode, n, batch, E, _ptr(xT), C.cast(fn, C.c_void_p), None,
+                                 _ptr(x0), None, 0, None)
+        if rc != 0:
+            raise ValueError("oracle rejected sample arguments")
+        return x0
+
+    # ---- DiT
+    @staticmethod
+    def dit_config(d):
+        return DitConfig(d["depth"], d["hidden"], d["heads"], d["mlp_ratio"], d["patch"], d["in_ch"],
+                         d["lat_h"], d["lat_w"], d["cond"], d["cond_dim"], d["ctx_len"],
+                         1 if d["dtype"] == 1 else 0)
+
+    def weight_count(self, d):
+        cfg = self.dit_config(d)
+        return int(self.lib.orc_weight_count(C.byref(cfg)))
+
+    def _cond(self, d, cond):
+        if cond is None:
+            return None
+        if d["cond"] == 1:
+            return np.ascontiguousarray(cond, np.int32)
+        return np.ascontiguousarray(cond, self.real)
+
+    def prepare_weights(self, w):
+        """Convert the flat fp32 weights to the oracle's real type once."""
+        return np.ascontiguousarray(w, self.real)
+
+    def dit_eps(self, d, w, x, t, cond, stop_blocks=-1):
+        cfg = self.dit_config(d)
+        w = self.prepare_weights(w)
+        assert w.size == self.weight_count(d)
+        x = np.ascontiguousarray(x, self.real)
+        t = np.ascontiguousarray(t, np.int32)
+        slots = x.shape[0]
+        cond = self._cond(d, cond)
+        if stop_blocks >= 0:
+            T = (d["lat_h"] // d["patch"]) * (d["lat_w"] // d["patch"])
+            res = np.empty((slots, T, d["hidden"]), self.real)
+            rc = self.lib.orc_dit_eps(C.byref(cfg), _ptr(w), _ptr(x), _ptr(t), _ptr(cond), slots, None,
+                                      stop_blocks, _ptr(res))
+            assert rc == 0
+            return res
+        out = np.empty_like(x)
+        rc = self.lib.orc_dit_eps(C.byref(cfg), _ptr(w), _ptr(x), _ptr(t), _ptr(cond), slots, _ptr(out),
+                                  -1, None)
+        assert rc == 0
+        return out
+
+    def eps_guided(self, d, w, x, tau, cond, null_cond, guidance):
+        cfg = self.dit_config(d)
+        w = self.prepare_weights(w)
+        x = np.ascontiguousarray(x, self.real)
+        out = np.empty_like(x)
+        cond, null_cond = self._cond(d, cond), self._cond(d, null_cond)
+        self.lib.orc_eps_guided(C.byref(cfg), _ptr(w), _ptr(x), tau, _ptr(cond), _ptr(null_cond),
+                                float(guidance or 0.0), x.shape[0], _ptr(out))
+        return out
+
+    def sample_dit(self, d, w, sd, mode, n, xT, cond, null_cond=None, guidance=0.0):
+        cfg = self.dit_config(d)
+        w = self.prepare_weights(w)
+        xT = np.ascontiguousarray(xT, self.real)
+        x0 = np.empty_like(xT)
+        sc = self.sched(sd)
+        cond, null_cond = self._cond(d, cond), self._cond(d, null_cond)
+        rc = self.lib.orc_sample_dit(C.byref(cfg), _ptr(w), C.byref(sc), mode, n, xT.shape[0], _ptr(xT),
+                                     _ptr(cond), _ptr(null_cond), float(guidance or 0.0), _ptr(x0))
+        if rc != 0:
+            raise ValueError("oracle rejected sample arguments")
+        return x0
