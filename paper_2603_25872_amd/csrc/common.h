@@ -1,0 +1,120 @@
+// Internal declarations shared by the translation units of libdrf.
+#pragma once
+#include <hip/hip_runtime.h>
+#include <stdint.h>
+#include <stddef.h>
+#include <string>
+#include <vector>
+
+#include "../../include/drf.h"
+
+namespace drf {
+
+// ---- errors -----------------------------------------------------------------
+void set_error(const char* fmt, ...);
+#define DRF_FAIL(code, ...) do { ::drf::set_error(__VA_ARGS__); return (code); } while (0)
+#define DRF_HIP(expr) do { hipError_t e_ = (expr); if (e_ != hipSuccess) { \
+    ::drf::set_error("%s failed: %s (%s:%d)", #expr, hipGetErrorString(e_), __FILE__, __LINE__); \
+    return DRF_EHIP; } } while (0)
+
+// ---- schedule / plan (host) ---------------------------------------------------
+struct Schedule {
+    std::vector<double> abar;   // cumulative alpha per training timestep
+    int steps = 0, stride = 0;
+    int tau(int s) const { return (s - 1) * stride; }
+    double abar_at(int s) const { return s == 0 ? 1.0 : abar[(size_t)tau(s)]; }
+    // x_to = A x_from + B eps
+    void coef(int s_from, int s_to, float* A, float* B) const;
+};
+drf_status make_schedule(const drf_sched_config* sc, Schedule* out);
+
+// One batched predictor pass of drf_sample and the elementwise update after it.
+struct Pass {
+    int round = 0;
+    bool solo = false;              // stand-alone evaluation of the anchor state
+    int s_anchor = 0;               // anchor index the evaluated states were drafted from
+    std::vector<int> eval_s;        // sampling indices evaluated, one per slot group
+    bool base_is_draft = false;     // chain starts from the first draft, else from the anchor state
+    std::vector<std::pair<int, int>> chain;   // standard updates (s_from -> s_to); update i uses noise field i
+    int anchor_field = -1;          // noise field that pairs with the state after the chain (-1: none)
+    std::vector<int> draft_to;      // skip targets drafted from (state after chain, anchor noise)
+    int s_after = 0;                // index of the state after the chain
+    bool writes_x0 = false;         // the state after the chain (or the lone draft to 0) is x_0
+};
+// rows: plan table in the documented row format (may be NULL).
+drf_status build_plan(const Schedule& sch, drf_mode mode, int n, std::vector<Pass>* passes,
+                      std::vector<int32_t>* rows);
+
+// ---- elementwise update kernel --------------------------------------------------
+constexpr int kMaxBlock = 64;       // largest block size n the update kernel's argument block holds
+struct UpdateArgs {
+    const float* x_base;   // [field]
+    const float* eps;      // [n_fields][g][field]
+    float* x_out;          // [field] or NULL: state after the chain
+    float* draft_out;      // [n_draft][field] or NULL
+    size_t field;          // batch * elems_per_sample
+    int g;                 // 1, or 2 = (cond, null) pairs combined by guidance
+    float w;               // guidance scale
+    int n_chain, anchor_field, n_draft;
+    float cA[kMaxBlock], cB[kMaxBlock], dA[kMaxBlock], dB[kMaxBlock];
+};
+drf_status launch_update(const UpdateArgs& a, hipStream_t st);
+
+// ---- DiT kernels ------------------------------------------------------------------
+typedef __bf16 bf16_t;
+
+// How slot j of a pass finds its inputs.
+struct SlotMap {
+    const int32_t* t_dev;   // per-slot training timesteps, or NULL: use taus[j / group]
+    int group;              // slots per draft group (g * batch)
+    int taus[kMaxBlock];
+    int x_group, x_batch;   // x row of slot j = (j / x_group) * x_batch + j % x_batch
+    int cond_mod;           // cond row of slot j = cond_mod ? j % cond_mod : j
+};
+
+enum EpiMode { EPI_STORE = 0, EPI_STORE_GELU = 1, EPI_RESID = 2 };
+struct Epilogue {
+    int mode;
+    void* out;              // EPI_STORE*: [M][ldo] of out type; EPI_RESID: float [M][ldo], read-modify-write
+    int ldo;
+    int out_f32;            // EPI_STORE*: 1 = float output, 0 = bf16 output
+    const float* bias;      // [N]
+    const float* gate;      // EPI_RESID: gate[(m / rows_per_slot) * gate_ld + n], NULL = ungated
+    int gate_ld, rows_per_slot;
+};
+// C[M][N] = A[M][K] . W[N][K]^T, then the epilogue.  bf16: K % 64 == 0.
+drf_status launch_gemm_bf16(const bf16_t* A, const bf16_t* W, int M, int N, int K, const Epilogue& e, hipStream_t st);
+drf_status launch_gemm_f32(const float* A, const float* W, int M, int N, int K, const Epilogue& e, hipStream_t st);
+
+struct AttnArgs {
+    const void* q; int ldq;         // row (slot * Nq + i), head h at column h * d
+    const void* k; const void* v; int ldk;   // row (kv_batch * Nk + j)
+    void* out; int ldo;
+    int Nq, Nk, heads, d, slots;
+    int kv_mod;                     // kv_batch = kv_mod ? slot % kv_mod : slot
+};
+drf_status launch_attn_bf16(const AttnArgs& a, hipStream_t st);
+drf_status launch_attn_f32(const AttnArgs& a, hipStream_t st);
+
+struct DitDims { int D, P, T, gh, gw, C, H, W, patch, heads, d, R, L; };
+
+// c = MLP(femb(tau)) + cond embedding; writes SiLU(c) as float [slots][D] and, if act_bf16 != NULL, bf16.
+struct CondArgs {
+    const float *t_w1, *t_b1, *t_w2, *t_b2, *c_w, *c_b, *table;
+    const void* cond; int cond_kind, cond_dim;
+    int D, slots;
+    SlotMap map;
+    float* act_f32; bf16_t* act_bf16;
+};
+drf_status launch_cond_embed(const CondArgs& a, hipStream_t st);
+
+drf_status launch_patch_embed(const float* x, const SlotMap& map, const float* w, const float* b, const float* pos,
+                              const DitDims& dm, int slots, float* resid, hipStream_t st);
+// out = LN(resid) * (1 + scale) + shift (shift == NULL: plain LN); mod rows are per slot.
+drf_status launch_ln_modulate(const float* resid, const float* shift, const float* scale, int mod_ld, int rows_per_slot,
+                              int M, int D, void* out, int out_f32, hipStream_t st);
+drf_status launch_final(const float* resid, const float* shift, const float* scale, int mod_ld, const float* w,
+                        const float* b, const DitDims& dm, int slots, float* eps_out, hipStream_t st);
+drf_status launch_f32_to_bf16(const float* in, bf16_t* out, size_t n, hipStream_t st);
+
+}  // namespace drf

@@ -1,0 +1,588 @@
+// The denoiser handle, the batched DiT forward and the draft-and-refine loop.
+#include <cmath>
+#include <cstring>
+
+#include "common.h"
+
+using namespace drf;
+
+namespace {
+
+constexpr int kTFreq = 256;
+
+struct LinearW {
+    const float* w32 = nullptr;     // fp32 path weights [N][K]
+    const bf16_t* w16 = nullptr;    // bf16 path weights [N][K]
+    const float* b = nullptr;       // bias [N] fp32
+    int N = 0, K = 0;
+};
+
+struct BlockW { LinearW qkv, proj, xq, xkv, xo, fc1, fc2; };
+
+struct Prof {
+    bool on = false;
+    std::vector<hipEvent_t> pool;
+    struct Rec { int fam; size_t e0, e1; double work; };
+    std::vector<Rec> recs;
+    size_t used = 0;
+};
+
+}  // namespace
+
+struct drf_denoiser {
+    drf_dit_config cfg{};
+    DitDims dm{};
+    bool bf16 = false;
+    int n_mod = 0;                  // 6 L D + 2 D modulation columns per slot
+    std::vector<void*> allocs;      // everything freed at destroy
+    // parameters on the device
+    float* params32 = nullptr;      // the whole flat array (rounded to bf16 values in bf16 mode)
+    const float *patch_w = nullptr, *patch_b = nullptr, *t_w1 = nullptr, *t_b1 = nullptr, *t_w2 = nullptr,
+                *t_b2 = nullptr, *c_w = nullptr, *c_b = nullptr, *table = nullptr, *fin_w = nullptr, *fin_b = nullptr;
+    LinearW ada;                    // all blocks' adaLN projections and the final one, stacked [n_mod][D]
+    std::vector<BlockW> blk;
+    float* pos = nullptr;           // [T][D]
+    // workspace
+    int cap_slots = 0;
+    float *resid = nullptr, *mod = nullptr, *cact32 = nullptr;
+    void *hbuf = nullptr, *qkv = nullptr, *mid = nullptr, *cact = nullptr;
+    // cross-attention K/V cache [L][rows][ctx_len][2D] and its staging
+    void* xkv = nullptr; void* ctx_act = nullptr; int cap_ctx_rows = 0;
+    // sampler buffers
+    int cap_sample_n = 0, cap_sample_field = 0, cap_sample_g = 0;
+    float *drafts = nullptr, *epsbuf = nullptr, *anchor = nullptr;
+    void* cond_cat = nullptr; size_t cond_cat_bytes = 0;
+    Prof prof;
+};
+
+namespace {
+
+drf_status dev_alloc(drf_denoiser* d, void** p, size_t bytes)
+{
+    *p = nullptr;
+    if (bytes == 0) bytes = 16;
+    if (hipMalloc(p, bytes) != hipSuccess) {
+        (void)hipGetLastError();
+        DRF_FAIL(DRF_ENOMEM, "device allocation of %zu bytes failed", bytes);
+    }
+    d->allocs.push_back(*p);
+    return DRF_OK;
+}
+
+void dev_free(drf_denoiser* d, void* p)
+{
+    if (!p) return;
+    for (size_t i = 0; i < d->allocs.size(); ++i)
+        if (d->allocs[i] == p) { d->allocs.erase(d->allocs.begin() + (long)i); break; }
+    (void)hipFree(p);
+}
+
+drf_status check_config(const drf_dit_config* c)
+{
+    if (!c) DRF_FAIL(DRF_EINVAL, "config is NULL");
+    if (c->depth < 0 || c->hidden < 4 || c->heads < 1 || c->mlp_ratio < 1 || c->patch < 1 || c->in_ch < 1 ||
+        c->lat_h < 1 || c->lat_w < 1)
+        DRF_FAIL(DRF_EINVAL, "non-positive DiT dimension");
+    if (c->dtype != DRF_F32 && c->dtype != DRF_BF16) DRF_FAIL(DRF_EINVAL, "unknown dtype");
+    if (c->cond != DRF_COND_VECTOR && c->cond != DRF_COND_CLASS && c->cond != DRF_COND_TEXT) DRF_FAIL(DRF_EINVAL, "unknown cond kind");
+    if (c->cond_dim < 1) DRF_FAIL(DRF_EINVAL, "cond_dim must be >= 1");
+    if (c->cond == DRF_COND_TEXT ? c->ctx_len < 1 : c->ctx_len != 0) DRF_FAIL(DRF_EINVAL, "ctx_len must be >= 1 for text and 0 otherwise");
+    if (c->hidden % c->heads || c->hidden % 4 || c->lat_h % c->patch || c->lat_w % c->patch)
+        DRF_FAIL(DRF_ESHAPE, "need hidden %% heads == 0, hidden %% 4 == 0 and latent divisible by patch");
+    const int d = c->hidden / c->heads;
+    if (c->dtype == DRF_BF16) {
+        if (c->hidden % 64 || d % 8 || d > 96) DRF_FAIL(DRF_ESHAPE, "bf16 needs hidden %% 64 == 0, head dim %% 8 == 0 and <= 96");
+        if (c->cond == DRF_COND_TEXT && c->cond_dim % 64) DRF_FAIL(DRF_ESHAPE, "bf16 text conditioning needs cond_dim %% 64 == 0");
+    } else if (d > 128) {
+        DRF_FAIL(DRF_ESHAPE, "fp32 needs head dim <= 128");
+    }
+    if (c->hidden > 2048) DRF_FAIL(DRF_ESHAPE, "hidden must be <= 2048");
+    return DRF_OK;
+}
+
+size_t weight_count(const drf_dit_config* c)
+{
+    const size_t D = (size_t)c->hidden, P = (size_t)c->in_ch * c->patch * c->patch, R = (size_t)c->mlp_ratio;
+    size_t n = D * P + D + D * kTFreq + D + D * D + D;
+    if (c->cond == DRF_COND_VECTOR) n += D * (size_t)c->cond_dim + D;
+    else if (c->cond == DRF_COND_CLASS) n += ((size_t)c->cond_dim + 1) * D;
+    size_t per = 6 * D * D + 6 * D + 3 * D * D + 3 * D + D * D + D + R * D * D + R * D + D * R * D + D;
+    if (c->cond == DRF_COND_TEXT) per += D * D + D + 2 * D * (size_t)c->cond_dim + 2 * D + D * D + D;
+    n += per * (size_t)c->depth;
+    n += 2 * D * D + 2 * D + P * D + P;
+    return n;
+}
+
+// round-to-nearest-even to bf16, kept in fp32
+inline float rne_bf16(float f)
+{
+    uint32_t u;
+    std::memcpy(&u, &f, 4);
+    if ((u & 0x7f800000u) != 0x7f800000u) u += 0x7fffu + ((u >> 16) & 1u);
+    u &= 0xffff0000u;
+    std::memcpy(&f, &u, 4);
+    return f;
+}
+
+struct ProfScope {
+    drf_denoiser* d; hipStream_t st; bool live = false; size_t rec = 0;
+    ProfScope(drf_denoiser* d_, hipStream_t st_, int fam, double work) : d(d_), st(st_)
+    {
+        Prof& p = d->prof;
+        if (!p.on) return;
+        while (p.pool.size() < p.used + 2) {
+            hipEvent_t ev;
+            if (hipEventCreate(&ev) != hipSuccess) return;
+            p.pool.push_back(ev);
+        }
+        live = true;
+        p.recs.push_back({ fam, p.used, p.used + 1, work });
+        rec = p.recs.size() - 1;
+        (void)hipEventRecord(p.pool[p.used], st);
+        p.used += 2;
+    }
+    ~ProfScope() { if (live) (void)hipEventRecord(d->prof.pool[d->prof.recs[rec].e1], st); }
+};
+
+drf_status ensure_workspace(drf_denoiser* d, int slots, hipStream_t st)
+{
+    if (slots <= d->cap_slots) return DRF_OK;
+    DRF_HIP(hipStreamSynchronize(st));
+    void* olds[] = { d->resid, d->mod, d->cact32, d->hbuf, d->qkv, d->mid, d->cact };
+    for (void* p : olds) dev_free(d, p);
+    d->cap_slots = 0;
+    const size_t M = (size_t)slots * d->dm.T, D = (size_t)d->dm.D, act = d->bf16 ? 2 : 4;
+    drf_status rc;
+    if ((rc = dev_alloc(d, (void**)&d->resid, M * D * 4)) != DRF_OK) return rc;
+    if ((rc = dev_alloc(d, (void**)&d->mod, (size_t)slots * d->n_mod * 4)) != DRF_OK) return rc;
+    if ((rc = dev_alloc(d, (void**)&d->cact32, (size_t)slots * D * 4)) != DRF_OK) return rc;
+    if ((rc = dev_alloc(d, &d->cact, (size_t)slots * D * act)) != DRF_OK) return rc;
+    if ((rc = dev_alloc(d, &d->hbuf, M * D * act)) != DRF_OK) return rc;
+    if ((rc = dev_alloc(d, &d->qkv, M * 3 * D * act)) != DRF_OK) return rc;
+    if ((rc = dev_alloc(d, &d->mid, M * (size_t)d->dm.R * D * act)) != DRF_OK) return rc;
+    d->cap_slots = slots;
+    return DRF_OK;
+}
+
+drf_status ensure_ctx(drf_denoiser* d, int rows, hipStream_t st)
+{
+    if (d->cfg.cond != DRF_COND_TEXT || rows <= d->cap_ctx_rows) return DRF_OK;
+    DRF_HIP(hipStreamSynchronize(st));
+    dev_free(d, d->xkv); dev_free(d, d->ctx_act);
+    d->cap_ctx_rows = 0;
+    const size_t act = d->bf16 ? 2 : 4, rl = (size_t)rows * d->cfg.ctx_len;
+    drf_status rc;
+    if ((rc = dev_alloc(d, &d->xkv, (size_t)d->dm.L * rl * 2 * d->dm.D * act)) != DRF_OK) return rc;
+    if ((rc = dev_alloc(d, &d->ctx_act, rl * d->cfg.cond_dim * act)) != DRF_OK) return rc;
+    d->cap_ctx_rows = rows;
+    return DRF_OK;
+}
+
+drf_status gemm(drf_denoiser* d, const void* A, const LinearW& w, int M, Epilogue e, hipStream_t st)
+{
+    e.bias = w.b;
+    ProfScope ps(d, st, DRF_PROF_GEMM, 2.0 * M * (double)w.N * w.K);
+    if (d->bf16) return launch_gemm_bf16((const bf16_t*)A, w.w16, M, w.N, w.K, e, st);
+    return launch_gemm_f32((const float*)A, w.w32, M, w.N, w.K, e, st);
+}
+
+Epilogue epi_store(void* out, int ldo, bool f32, bool gelu = false)
+{
+    Epilogue e{};
+    e.mode = gelu ? EPI_STORE_GELU : EPI_STORE; e.out = out; e.ldo = ldo; e.out_f32 = f32 ? 1 : 0;
+    return e;
+}
+
+Epilogue epi_resid(float* resid, int ldo, const float* gate, int gate_ld, int rows_per_slot)
+{
+    Epilogue e{};
+    e.mode = EPI_RESID; e.out = resid; e.ldo = ldo; e.out_f32 = 1; e.gate = gate; e.gate_ld = gate_ld;
+    e.rows_per_slot = rows_per_slot;
+    return e;
+}
+
+// K/V of the text context for every block: xkv[l][row][ctx][2D] = Linear(ctx[row]).
+drf_status compute_ctx_kv(drf_denoiser* d, const float* ctx, int rows, hipStream_t st)
+{
+    drf_status rc = ensure_ctx(d, rows, st);
+    if (rc != DRF_OK) return rc;
+    const size_t rl = (size_t)rows * d->cfg.ctx_len, act = d->bf16 ? 2 : 4;
+    const void* A = ctx;
+    if (d->bf16) {
+        ProfScope ps(d, st, DRF_PROF_ELEMWISE, 6.0 * rl * d->cfg.cond_dim);
+        if ((rc = launch_f32_to_bf16(ctx, (bf16_t*)d->ctx_act, rl * d->cfg.cond_dim, st)) != DRF_OK) return rc;
+        A = d->ctx_act;
+    }
+    for (int l = 0; l < d->dm.L; ++l) {
+        void* out = (char*)d->xkv + (size_t)l * rl * 2 * d->dm.D * act;
+        if ((rc = gemm(d, A, d->blk[l].xkv, (int)rl, epi_store(out, 2 * d->dm.D, !d->bf16), st)) != DRF_OK) return rc;
+    }
+    return DRF_OK;
+}
+
+// The batched forward.  ctx_rows > 0: the cross-attention K/V cache already holds that many rows.
+drf_status forward(drf_denoiser* d, const float* x, const SlotMap& map, const void* cond, int slots, int n_blocks,
+                   float* eps_out, float* resid_out, hipStream_t st)
+{
+    const DitDims& dm = d->dm;
+    const int D = dm.D, M = slots * dm.T, nm = d->n_mod;
+    const bool f32 = !d->bf16;
+    drf_status rc;
+    if ((rc = ensure_workspace(d, slots, st)) != DRF_OK) return rc;
+
+    {   // conditioning: c per slot, then every block's shift/scale/gate in one GEMM
+        CondArgs ca{};
+        ca.t_w1 = d->t_w1; ca.t_b1 = d->t_b1; ca.t_w2 = d->t_w2; ca.t_b2 = d->t_b2; ca.c_w = d->c_w; ca.c_b = d->c_b;
+        ca.table = d->table; ca.cond = cond; ca.cond_kind = d->cfg.cond; ca.cond_dim = d->cfg.cond_dim; ca.D = D;
+        ca.slots = slots; ca.map = map; ca.act_f32 = d->cact32; ca.act_bf16 = d->bf16 ? (bf16_t*)d->cact : nullptr;
+        {
+            ProfScope ps(d, st, DRF_PROF_ELEMWISE, 4.0 * slots * ((double)kTFreq * D + (double)D * D));
+            if ((rc = launch_cond_embed(ca, st)) != DRF_OK) return rc;
+        }
+        const void* A = d->bf16 ? d->cact : (const void*)d->cact32;
+        if ((rc = gemm(d, A, d->ada, slots, epi_store(d->mod, nm, true), st)) != DRF_OK) return rc;
+    }
+    {
+        ProfScope ps(d, st, DRF_PROF_ELEMWISE, (double)M * D * 8.0 + (double)M * dm.P * 4.0);
+        if ((rc = launch_patch_embed(x, map, d->patch_w, d->patch_b, d->pos, dm, slots, d->resid, st)) != DRF_OK) return rc;
+    }
+    const double ln_bytes = (double)M * D * (4.0 + (f32 ? 4.0 : 2.0));
+    const size_t act = f32 ? 4 : 2;
+    for (int l = 0; l < n_blocks; ++l) {
+        const BlockW& b = d->blk[l];
+        const float* mrow = d->mod + (size_t)l * 6 * D;     // shift1 | scale1 | gate1 | shift2 | scale2 | gate2
+        {
+            ProfScope ps(d, st, DRF_PROF_ELEMWISE, ln_bytes);
+            if ((rc = launch_ln_modulate(d->resid, mrow, mrow + D, nm, dm.T, M, D, d->hbuf, f32, st)) != DRF_OK) return rc;
+        }
+        if ((rc = gemm(d, d->hbuf, b.qkv, M, epi_store(d->qkv, 3 * D, f32), st)) != DRF_OK) return rc;
+        {
+            AttnArgs aa{};
+            aa.q = d->qkv; aa.ldq = 3 * D; aa.k = (char*)d->qkv + (size_t)D * act; aa.v = (char*)d->qkv + (size_t)2 * D * act;
+            aa.ldk = 3 * D; aa.out = d->hbuf; aa.ldo = D; aa.Nq = dm.T; aa.Nk = dm.T; aa.heads = dm.heads; aa.d = dm.d;
+            aa.slots = slots; aa.kv_mod = 0;
+            ProfScope ps(d, st, DRF_PROF_ATTN, 4.0 * slots * dm.heads * (double)dm.T * dm.T * dm.d);
+            if ((rc = f32 ? launch_attn_f32(aa, st) : launch_attn_bf16(aa, st)) != DRF_OK) return rc;
+        }
+        if ((rc = gemm(d, d->hbuf, b.proj, M, epi_resid(d->resid, D, mrow + 2 * D, nm, dm.T), st)) != DRF_OK) return rc;
+        if (d->cfg.cond == DRF_COND_TEXT) {
+            const int ctx_rows = map.cond_mod ? map.cond_mod : slots;
+            {
+                ProfScope ps(d, st, DRF_PROF_ELEMWISE, ln_bytes);
+                if ((rc = launch_ln_modulate(d->resid, nullptr, nullptr, 0, dm.T, M, D, d->hbuf, f32, st)) != DRF_OK) return rc;
+            }
+            if ((rc = gemm(d, d->hbuf, b.xq, M, epi_store(d->qkv, D, f32), st)) != DRF_OK) return rc;
+            const char* kv = (const char*)d->xkv + (size_t)l * ctx_rows * d->cfg.ctx_len * 2 * D * act;
+            AttnArgs aa{};
+            aa.q = d->qkv; aa.ldq = D; aa.k = kv; aa.v = kv + (size_t)D * act; aa.ldk = 2 * D; aa.out = d->hbuf; aa.ldo = D;
+            aa.Nq = dm.T; aa.Nk = d->cfg.ctx_len; aa.heads = dm.heads; aa.d = dm.d; aa.slots = slots; aa.kv_mod = map.cond_mod;
+            {
+                ProfScope ps(d, st, DRF_PROF_ATTN, 4.0 * slots * dm.heads * (double)dm.T * d->cfg.ctx_len * dm.d);
+                if ((rc = f32 ? launch_attn_f32(aa, st) : launch_attn_bf16(aa, st)) != DRF_OK) return rc;
+            }
+            if ((rc = gemm(d, d->hbuf, b.xo, M, epi_resid(d->resid, D, nullptr, 0, dm.T), st)) != DRF_OK) return rc;
+        }
+        {
+            ProfScope ps(d, st, DRF_PROF_ELEMWISE, ln_bytes);
+            if ((rc = launch_ln_modulate(d->resid, mrow + 3 * D, mrow + 4 * D, nm, dm.T, M, D, d->hbuf, f32, st)) != DRF_OK) return rc;
+        }
+        if ((rc = gemm(d, d->hbuf, b.fc1, M, epi_store(d->mid, dm.R * D, f32, true), st)) != DRF_OK) return rc;
+        if ((rc = gemm(d, d->mid, b.fc2, M, epi_resid(d->resid, D, mrow + 5 * D, nm, dm.T), st)) != DRF_OK) return rc;
+    }
+    if (resid_out) {
+        DRF_HIP(hipMemcpyAsync(resid_out, d->resid, (size_t)M * D * 4, hipMemcpyDeviceToDevice, st));
+        return DRF_OK;
+    }
+    const float* fm = d->mod + (size_t)dm.L * 6 * D;        // final shift | scale
+    ProfScope ps(d, st, DRF_PROF_ELEMWISE, (double)M * D * 4.0 + (double)M * dm.P * 4.0);
+    return launch_final(d->resid, fm, fm + D, nm, d->fin_w, d->fin_b, dm, slots, eps_out, st);
+}
+
+SlotMap identity_map(const int32_t* t)
+{
+    SlotMap m{};
+    m.t_dev = t; m.group = 1; m.x_group = 1; m.x_batch = 1; m.cond_mod = 0;
+    return m;
+}
+
+drf_status eps_common(drf_denoiser* den, const float* x, const int32_t* t, const void* cond, int slots, int n_blocks,
+                      float* eps_out, float* resid_out, hipStream_t st)
+{
+    if (!den) DRF_FAIL(DRF_EINVAL, "denoiser is NULL");
+    if (slots < 0) DRF_FAIL(DRF_EINVAL, "slots must be >= 0");
+    if (slots == 0) return DRF_OK;
+    if (!x || !t || !cond || (!eps_out && !resid_out)) DRF_FAIL(DRF_EINVAL, "NULL buffer");
+    if ((size_t)slots * den->dm.T > (size_t)1 << 30) DRF_FAIL(DRF_EINVAL, "slots * tokens too large");
+    drf_status rc;
+    if (den->cfg.cond == DRF_COND_TEXT && (rc = compute_ctx_kv(den, (const float*)cond, slots, st)) != DRF_OK) return rc;
+    return forward(den, x, identity_map(t), cond, slots, n_blocks, eps_out, resid_out, st);
+}
+
+}  // namespace
+
+extern "C" size_t drf_denoiser_weight_count(const drf_dit_config* cfg)
+{
+    if (check_config(cfg) != DRF_OK) return 0;
+    return weight_count(cfg);
+}
+
+extern "C" drf_status drf_denoiser_create(const drf_dit_config* cfg, const float* host_weights, size_t count,
+                                          void* hip_stream, drf_denoiser** out)
+{
+    drf_status rc = check_config(cfg);
+    if (rc != DRF_OK) return rc;
+    if (!host_weights || !out) DRF_FAIL(DRF_EINVAL, "NULL argument");
+    *out = nullptr;
+    const size_t want = weight_count(cfg);
+    if (count != want) DRF_FAIL(DRF_EINVAL, "weight count %zu does not match configuration (%zu)", count, want);
+    hipStream_t st = (hipStream_t)hip_stream;
+    int ndev = 0;
+    if (hipGetDeviceCount(&ndev) != hipSuccess || ndev < 1) { (void)hipGetLastError(); DRF_FAIL(DRF_EHIP, "no HIP device available"); }
+
+    drf_denoiser* d = new (std::nothrow) drf_denoiser();
+    if (!d) DRF_FAIL(DRF_ENOMEM, "host allocation failed");
+    d->cfg = *cfg;
+    d->bf16 = cfg->dtype == DRF_BF16;
+    DitDims& dm = d->dm;
+    dm.D = cfg->hidden; dm.P = cfg->in_ch * cfg->patch * cfg->patch; dm.gh = cfg->lat_h / cfg->patch; dm.gw = cfg->lat_w / cfg->patch;
+    dm.T = dm.gh * dm.gw; dm.C = cfg->in_ch; dm.H = cfg->lat_h; dm.W = cfg->lat_w; dm.patch = cfg->patch; dm.heads = cfg->heads;
+    dm.d = cfg->hidden / cfg->heads; dm.R = cfg->mlp_ratio; dm.L = cfg->depth;
+    d->n_mod = 6 * dm.L * dm.D + 2 * dm.D;
+    const size_t D = (size_t)dm.D, P = (size_t)dm.P, R = (size_t)dm.R;
+
+    auto fail = [&](drf_status s) { drf_denoiser_destroy(d); return s; };
+
+    // In bf16 mode every parameter takes its bf16 value first (round-to-nearest-even).
+    std::vector<float> rounded;
+    const float* src = host_weights;
+    if (d->bf16) {
+        rounded.resize(count);
+        for (size_t i = 0; i < count; ++i) rounded[i] = rne_bf16(host_weights[i]);
+        src = rounded.data();
+    }
+    if ((rc = dev_alloc(d, (void**)&d->params32, count * 4)) != DRF_OK) return fail(rc);
+    if (hipMemcpy(d->params32, src, count * 4, hipMemcpyHostToDevice) != hipSuccess) { set_error("weight upload failed"); return fail(DRF_EHIP); }
+
+    // Walk the documented order; collect matrices that the GEMMs use.
+    size_t off = 0;
+    auto take = [&](size_t n) { const float* p = d->params32 + off; off += n; return p; };
+    struct Pending { LinearW* lw; size_t woff; };
+    std::vector<Pending> mats;
+    auto take_linear = [&](LinearW* lw, size_t N, size_t K) {
+        mats.push_back({ lw, off });
+        lw->w32 = take(N * K); lw->b = take(N); lw->N = (int)N; lw->K = (int)K;
+    };
+    d->patch_w = take(D * P); d->patch_b = take(D);
+    d->t_w1 = take(D * kTFreq); d->t_b1 = take(D); d->t_w2 = take(D * D); d->t_b2 = take(D);
+    if (cfg->cond == DRF_COND_VECTOR) { d->c_w = take(D * (size_t)cfg->cond_dim); d->c_b = take(D); }
+    else if (cfg->cond == DRF_COND_CLASS) d->table = take(((size_t)cfg->cond_dim + 1) * D);
+    d->blk.resize((size_t)dm.L);
+    std::vector<size_t> ada_w_off((size_t)dm.L + 1), ada_b_off((size_t)dm.L + 1);
+    for (int l = 0; l < dm.L; ++l) {
+        BlockW& b = d->blk[(size_t)l];
+        ada_w_off[(size_t)l] = off; take(6 * D * D); ada_b_off[(size_t)l] = off; take(6 * D);
+        take_linear(&b.qkv, 3 * D, D);
+        take_linear(&b.proj, D, D);
+        if (cfg->cond == DRF_COND_TEXT) {
+            take_linear(&b.xq, D, D);
+            take_linear(&b.xkv, 2 * D, (size_t)cfg->cond_dim);
+            take_linear(&b.xo, D, D);
+        }
+        take_linear(&b.fc1, R * D, D);
+        take_linear(&b.fc2, D, R * D);
+    }
+    ada_w_off[(size_t)dm.L] = off; take(2 * D * D); ada_b_off[(size_t)dm.L] = off; take(2 * D);
+    d->fin_w = take(P * D); d->fin_b = take(P);
+    if (off != count) { set_error("internal: parameter walk mismatch"); return fail(DRF_EINVAL); }
+
+    // Stack the adaLN projections of all blocks and of the final layer into one [n_mod][D] matrix.
+    float *ada_w = nullptr, *ada_b = nullptr;
+    if ((rc = dev_alloc(d, (void**)&ada_w, (size_t)d->n_mod * D * 4)) != DRF_OK) return fail(rc);
+    if ((rc = dev_alloc(d, (void**)&ada_b, (size_t)d->n_mod * 4)) != DRF_OK) return fail(rc);
+    for (int l = 0; l <= dm.L; ++l) {
+        const size_t rows = (l < dm.L ? 6 : 2) * D, r0 = (size_t)l * 6 * D;
+        if (hipMemcpy(ada_w + r0 * D, d->params32 + ada_w_off[(size_t)l], rows * D * 4, hipMemcpyDeviceToDevice) != hipSuccess ||
+            hipMemcpy(ada_b + r0, d->params32 + ada_b_off[(size_t)l], rows * 4, hipMemcpyDeviceToDevice) != hipSuccess) {
+            set_error("adaLN repack failed");
+            return fail(DRF_EHIP);
+        }
+    }
+    d->ada.w32 = ada_w; d->ada.b = ada_b; d->ada.N = d->n_mod; d->ada.K = dm.D;
+    mats.push_back({ &d->ada, (size_t)-1 });
+
+    if (hipDeviceSynchronize() != hipSuccess) { set_error("create: device synchronise failed"); return fail(DRF_EHIP); }
+    if (d->bf16) {
+        for (Pending& pm : mats) {
+            const size_t n = (size_t)pm.lw->N * pm.lw->K;
+            bf16_t* w16 = nullptr;
+            if ((rc = dev_alloc(d, (void**)&w16, n * 2)) != DRF_OK) return fail(rc);
+            if ((rc = launch_f32_to_bf16(pm.lw->w32, w16, n, st)) != DRF_OK) return fail(rc);   // exact: values are bf16 already
+            pm.lw->w16 = w16;
+        }
+    }
+
+    // fixed 2-D sin-cos position code
+    {
+        std::vector<float> pos((size_t)dm.T * D);
+        const size_t q4 = D / 4;
+        for (int py = 0; py < dm.gh; ++py)
+            for (int px = 0; px < dm.gw; ++px) {
+                float* row = pos.data() + ((size_t)py * dm.gw + px) * D;
+                for (size_t i = 0; i < q4; ++i) {
+                    const double om = std::exp(-std::log(10000.0) * (double)i / (double)q4);
+                    row[i] = (float)std::sin(py * om); row[q4 + i] = (float)std::cos(py * om);
+                    row[2 * q4 + i] = (float)std::sin(px * om); row[3 * q4 + i] = (float)std::cos(px * om);
+                }
+            }
+        if ((rc = dev_alloc(d, (void**)&d->pos, pos.size() * 4)) != DRF_OK) return fail(rc);
+        if (hipMemcpy(d->pos, pos.data(), pos.size() * 4, hipMemcpyHostToDevice) != hipSuccess) { set_error("position code upload failed"); return fail(DRF_EHIP); }
+    }
+    if (hipStreamSynchronize(st) != hipSuccess) { set_error("create: stream synchronise failed"); return fail(DRF_EHIP); }
+    if (d->bf16) {
+        // the fp32 copies of the big matrices are no longer needed; keep params32 (small tensors point into it)
+        dev_free(d, ada_w);
+        d->ada.w32 = nullptr;
+    }
+    *out = d;
+    return DRF_OK;
+}
+
+extern "C" void drf_denoiser_destroy(drf_denoiser* den)
+{
+    if (!den) return;
+    for (void* p : den->allocs) (void)hipFree(p);
+    for (hipEvent_t ev : den->prof.pool) (void)hipEventDestroy(ev);
+    delete den;
+}
+
+extern "C" drf_status drf_denoiser_reserve(drf_denoiser* den, int max_slots)
+{
+    if (!den || max_slots < 0) DRF_FAIL(DRF_EINVAL, "bad argument");
+    return ensure_workspace(den, max_slots, nullptr);
+}
+
+extern "C" drf_status drf_eps_batched(drf_denoiser* den, const float* x, const int32_t* t, const void* cond, int slots,
+                                      float* eps_out, void* hip_stream)
+{
+    if (slots > 0 && !eps_out) DRF_FAIL(DRF_EINVAL, "eps_out is NULL");
+    return eps_common(den, x, t, cond, slots, den ? den->dm.L : 0, eps_out, nullptr, (hipStream_t)hip_stream);
+}
+
+extern "C" drf_status drf_eps_trace(drf_denoiser* den, const float* x, const int32_t* t, const void* cond, int slots,
+                                    int n_blocks, float* resid_out, void* hip_stream)
+{
+    if (!den) DRF_FAIL(DRF_EINVAL, "denoiser is NULL");
+    if (n_blocks < 0 || n_blocks > den->dm.L) DRF_FAIL(DRF_EINVAL, "n_blocks %d outside [0, %d]", n_blocks, den->dm.L);
+    if (slots > 0 && !resid_out) DRF_FAIL(DRF_EINVAL, "resid_out is NULL");
+    return eps_common(den, x, t, cond, slots, n_blocks, nullptr, resid_out, (hipStream_t)hip_stream);
+}
+
+extern "C" drf_status drf_sample(drf_denoiser* den, const drf_sched_config* sched, drf_mode mode, int n, int batch,
+                                 const float* x_T, const void* cond, const void* null_cond, float cfg_scale,
+                                 float* x_0_out, void* hip_stream)
+{
+    if (!den) DRF_FAIL(DRF_EINVAL, "denoiser is NULL");
+    Schedule sch;
+    drf_status rc = make_schedule(sched, &sch);
+    if (rc != DRF_OK) return rc;
+    if (batch < 0) DRF_FAIL(DRF_EINVAL, "batch must be >= 0");
+    if (n < 1) DRF_FAIL(DRF_EINVAL, "block size n must be >= 1 (got %d)", n);
+    if (n > sch.steps) n = sch.steps;               // larger blocks are cut at index 0 anyway
+    if (n > kMaxBlock) DRF_FAIL(DRF_EUNSUPPORTED, "block size n = %d exceeds the built maximum %d", n, kMaxBlock);
+    std::vector<Pass> passes;
+    if ((rc = build_plan(sch, mode, n, &passes, nullptr)) != DRF_OK) return rc;
+    if (batch == 0) return DRF_OK;
+    if (!x_T || !cond || !x_0_out) DRF_FAIL(DRF_EINVAL, "NULL buffer");
+    hipStream_t st = (hipStream_t)hip_stream;
+    const DitDims& dm = den->dm;
+    const int g = null_cond ? 2 : 1, gB = g * batch;
+    const size_t E = (size_t)dm.C * dm.H * dm.W, field = (size_t)batch * E;
+    if ((size_t)n * gB * dm.T > (size_t)1 << 30) DRF_FAIL(DRF_EINVAL, "n * batch * tokens too large");
+
+    // buffers: drafts [n][B][E], noises [n][g][B][E], anchor [B][E], conditioning rows [g*B]
+    if (n > den->cap_sample_n || (size_t)den->cap_sample_field < field || g > den->cap_sample_g) {
+        DRF_HIP(hipStreamSynchronize(st));
+        dev_free(den, den->drafts); dev_free(den, den->epsbuf); dev_free(den, den->anchor);
+        den->cap_sample_n = 0;
+        if ((rc = dev_alloc(den, (void**)&den->drafts, (size_t)n * field * 4)) != DRF_OK) return rc;
+        if ((rc = dev_alloc(den, (void**)&den->epsbuf, (size_t)n * g * field * 4)) != DRF_OK) return rc;
+        if ((rc = dev_alloc(den, (void**)&den->anchor, field * 4)) != DRF_OK) return rc;
+        den->cap_sample_n = n; den->cap_sample_field = (int)field; den->cap_sample_g = g;
+    }
+    size_t crow = 0;
+    switch (den->cfg.cond) {
+    case DRF_COND_VECTOR: crow = (size_t)den->cfg.cond_dim * 4; break;
+    case DRF_COND_CLASS: crow = 4; break;
+    default: crow = (size_t)den->cfg.ctx_len * den->cfg.cond_dim * 4; break;
+    }
+    if (den->cond_cat_bytes < crow * gB) {
+        DRF_HIP(hipStreamSynchronize(st));
+        dev_free(den, den->cond_cat);
+        den->cond_cat_bytes = 0;
+        if ((rc = dev_alloc(den, &den->cond_cat, crow * gB)) != DRF_OK) return rc;
+        den->cond_cat_bytes = crow * gB;
+    }
+    DRF_HIP(hipMemcpyAsync(den->cond_cat, cond, crow * batch, hipMemcpyDeviceToDevice, st));
+    if (g == 2) DRF_HIP(hipMemcpyAsync((char*)den->cond_cat + crow * batch, null_cond, crow * batch, hipMemcpyDeviceToDevice, st));
+    if ((rc = ensure_workspace(den, n * gB, st)) != DRF_OK) return rc;
+    // cross-attention K/V depend only on the context: once per call, for the g*B distinct rows
+    if (den->cfg.cond == DRF_COND_TEXT && (rc = compute_ctx_kv(den, (const float*)den->cond_cat, gB, st)) != DRF_OK) return rc;
+
+    const float* x_anchor = x_T;                    // state the next stand-alone pass evaluates
+    for (const Pass& p : passes) {
+        const int groups = (int)p.eval_s.size();
+        SlotMap map{};
+        map.t_dev = nullptr; map.group = gB; map.x_group = gB; map.x_batch = batch; map.cond_mod = gB;
+        for (int i = 0; i < groups; ++i) map.taus[i] = sch.tau(p.eval_s[(size_t)i]);
+        const float* xin = p.solo ? x_anchor : den->drafts;
+        if ((rc = forward(den, xin, map, den->cond_cat, groups * gB, dm.L, den->epsbuf, nullptr, st)) != DRF_OK) return rc;
+
+        UpdateArgs u{};
+        u.x_base = p.base_is_draft ? den->drafts : x_anchor;
+        u.eps = den->epsbuf; u.field = field; u.g = g; u.w = cfg_scale;
+        u.n_chain = (int)p.chain.size();
+        for (int i = 0; i < u.n_chain; ++i) sch.coef(p.chain[(size_t)i].first, p.chain[(size_t)i].second, &u.cA[i], &u.cB[i]);
+        u.anchor_field = p.anchor_field < 0 ? 0 : p.anchor_field;
+        u.n_draft = (int)p.draft_to.size();
+        for (int j = 0; j < u.n_draft; ++j) sch.coef(p.s_after, p.draft_to[(size_t)j], &u.dA[j], &u.dB[j]);
+        if (p.writes_x0) {
+            if (u.n_draft > 0) { u.draft_out = x_0_out; u.x_out = nullptr; }      // the lone draft to index 0 is x_0
+            else { u.x_out = x_0_out; u.draft_out = nullptr; }
+        } else if (u.n_draft > 0) {
+            // drafts overwrite the buffer the chain started from: each element is read before it is written
+            u.draft_out = den->drafts; u.x_out = nullptr;
+        } else {
+            u.x_out = den->anchor; u.draft_out = nullptr;
+            x_anchor = den->anchor;
+        }
+        const double bytes = (double)field * 4.0 * (1.0 + (double)g * (u.n_chain + (u.n_draft > 0 ? 1 : 0)) + (u.x_out ? 1 : 0) + u.n_draft);
+        ProfScope ps(den, st, DRF_PROF_UPDATE, bytes);
+        if ((rc = launch_update(u, st)) != DRF_OK) return rc;
+    }
+    return DRF_OK;
+}
+
+extern "C" drf_status drf_profile_enable(drf_denoiser* den, int on)
+{
+    if (!den) DRF_FAIL(DRF_EINVAL, "denoiser is NULL");
+    den->prof.on = on != 0;
+    return DRF_OK;
+}
+
+extern "C" drf_status drf_profile_read(drf_denoiser* den, int which, long long* launches, double* ms, double* work)
+{
+    if (!den || !launches || !ms || !work || which < 0 || which >= DRF_PROF_FAMILIES) DRF_FAIL(DRF_EINVAL, "bad argument");
+    DRF_HIP(hipDeviceSynchronize());
+    Prof& p = den->prof;
+    *launches = 0; *ms = 0.0; *work = 0.0;
+    std::vector<Prof::Rec> keep;
+    for (const Prof::Rec& r : p.recs) {
+        if (r.fam != which) { keep.push_back(r); continue; }
+        float t = 0.f;
+        if (hipEventElapsedTime(&t, p.pool[r.e0], p.pool[r.e1]) == hipSuccess) { *ms += t; *work += r.work; ++*launches; }
+        else (void)hipGetLastError();
+    }
+    p.recs.swap(keep);
+    if (p.recs.empty()) p.used = 0;
+    return DRF_OK;
+}

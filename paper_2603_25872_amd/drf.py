@@ -1,0 +1,203 @@
+"""Thin ctypes binding of libdrf's C ABI (see include/drf.h).
+
+Argument marshalling only: torch supplies device buffers and the current HIP stream;
+every step of the path runs in the library's kernels.  There is no CPU fallback: a
+missing library raises at load."""
+import ctypes as C
+import os
+
+import numpy as np
+
+HERE = os.path.dirname(os.path.abspath(__file__))
+LIB_PATH = os.path.join(HERE, "libdrf.so")
+
+CONSERVATIVE, AGGRESSIVE = 0, 1
+F32, BF16 = 0, 1
+COND_VECTOR, COND_CLASS, COND_TEXT = 0, 1, 2
+PLAN_ROW = 5
+PROF_GEMM, PROF_ATTN, PROF_ELEMWISE, PROF_UPDATE = 0, 1, 2, 3
+
+SYMBOLS = ["drf_denoiser_weight_count", "drf_denoiser_create", "drf_denoiser_destroy", "drf_denoiser_reserve",
+           "drf_eps_batched", "drf_eps_trace", "drf_skip_transition", "drf_refine_step", "drf_sample",
+           "drf_plan_build", "drf_profile_enable", "drf_profile_read", "drf_last_error"]
+
+
+class DitConfig(C.Structure):
+    _fields_ = [(k, C.c_int) for k in ("depth", "hidden", "heads", "mlp_ratio", "patch", "in_ch", "lat_h",
+                                         "lat_w", "dtype", "cond", "cond_dim", "ctx_len")]
+
+
+class SchedConfig(C.Structure):
+    _fields_ = [("train_steps", C.c_int), ("beta_start", C.c_double), ("beta_end", C.c_double),
+                ("steps", C.c_int), ("eta", C.c_double)]
+
+
+class DrfError(RuntimeError):
+    def __init__(self, status, msg):
+        super().__init__("libdrf status %d: %s" % (status, msg))
+        self.status = status
+
+
+_lib = None
+
+
+def lib():
+    """Load libdrf.so (built by paper_2603_25872_amd/build.py); raises if absent."""
+    global _lib
+    if _lib is None:
+        if not os.path.exists(LIB_PATH):
+            raise ImportError("libdrf.so is not built: run `python -m paper_2603_25872_amd.build`")
+        L = C.CDLL(LIB_PATH)
+        L.drf_denoiser_weight_count.restype = C.c_size_t
+        L.drf_denoiser_weight_count.argtypes = [C.c_void_p]
+        L.drf_denoiser_create.argtypes = [C.c_void_p, C.c_void_p, C.c_size_t, C.c_void_p, C.c_void_p]
+        L.drf_denoiser_destroy.argtypes = [C.c_void_p]
+        L.drf_denoiser_destroy.restype = None
+        L.drf_denoiser_reserve.argtypes = [C.c_void_p, C.c_int]
+        L.drf_eps_batched.argtypes = [C.c_void_p, C.c_void_p, C.c_void_p, C.c_void_p, C.c_int, C.c_void_p, C.c_void_p]
+        L.drf_eps_trace.argtypes = [C.c_void_p, C.c_void_p, C.c_void_p, C.c_void_p, C.c_int, C.c_int, C.c_void_p,
+                                    C.c_void_p]
+        L.drf_skip_transition.argtypes = [C.c_void_p, C.c_void_p, C.c_void_p, C.c_int, C.c_void_p, C.c_int, C.c_int,
+                                          C.c_size_t, C.c_void_p, C.c_void_p]
+        L.drf_refine_step.argtypes = [C.c_void_p, C.c_void_p, C.c_void_p, C.c_int, C.c_int, C.c_size_t, C.c_void_p,
+                                      C.c_void_p]
+        L.drf_sample.argtypes = [C.c_void_p, C.c_void_p, C.c_int, C.c_int, C.c_int, C.c_void_p, C.c_void_p,
+                                 C.c_void_p, C.c_float, C.c_void_p, C.c_void_p]
+        L.drf_plan_build.argtypes = [C.c_void_p, C.c_int, C.c_int, C.c_void_p, C.c_size_t, C.c_void_p]
+        L.drf_profile_enable.argtypes = [C.c_void_p, C.c_int]
+        L.drf_profile_read.argtypes = [C.c_void_p, C.c_int, C.c_void_p, C.c_void_p, C.c_void_p]
+        L.drf_last_error.restype = C.c_char_p
+        _lib = L
+    return _lib
+
+
+def _check(status):
+    if status != 0:
+        raise DrfError(status, lib().drf_last_error().decode())
+
+
+def dit_config(d):
+    return DitConfig(d["depth"], d["hidden"], d["heads"], d["mlp_ratio"], d["patch"], d["in_ch"], d["lat_h"],
+                     d["lat_w"], d["dtype"], d["cond"], d["cond_dim"], d["ctx_len"])
+
+
+def sched_config(d):
+    return SchedConfig(d["train_steps"], d["beta_start"], d["beta_end"], d["steps"], d.get("eta", 0.0))
+
+
+def _stream():
+    import torch
+    return C.c_void_p(torch.cuda.current_stream().cuda_stream)
+
+
+def _dev(t, dtype=None):
+    """Device pointer of a contiguous CUDA tensor."""
+    if t is None:
+        return None
+    assert t.is_cuda and t.is_contiguous(), "need a contiguous device tensor"
+    if dtype is not None:
+        assert t.dtype == dtype, "expected %s, got %s" % (dtype, t.dtype)
+    return C.c_void_p(t.data_ptr())
+
+
+def denoiser_weight_count(dit):
+    cfg = dit_config(dit)
+    return int(lib().drf_denoiser_weight_count(C.byref(cfg)))
+
+
+def plan_build(sched, mode, n):
+    """The bookkeeping table of drf_sample as an int32 array [rows, 5] (host only)."""
+    sc = sched_config(sched)
+    cnt = C.c_size_t(0)
+    _check(lib().drf_plan_build(C.byref(sc), mode, n, None, 0, C.byref(cnt)))
+    rows = np.zeros((cnt.value, PLAN_ROW), np.int32)
+    _check(lib().drf_plan_build(C.byref(sc), mode, n, rows.ctypes.data_as(C.c_void_p), cnt.value, C.byref(cnt)))
+    return rows
+
+
+def skip_transition(sched, x_from, eps_from, s_from, s_to, out=None):
+    """x_from, eps_from: fp32 device tensors [batch, ...]; s_to: list of target indices.
+    Returns [len(s_to), batch, ...]."""
+    import torch
+    sc = sched_config(sched)
+    m = len(s_to)
+    batch = x_from.shape[0] if x_from.dim() > 0 else 1
+    elems = x_from.numel() // batch if batch else 0
+    if out is None:
+        out = torch.empty((m,) + tuple(x_from.shape), dtype=torch.float32, device=x_from.device)
+    tgt = (C.c_int * max(m, 1))(*s_to)
+    _check(lib().drf_skip_transition(C.byref(sc), _dev(x_from, torch.float32), _dev(eps_from, torch.float32), s_from,
+                                     tgt, m, batch, elems, _dev(out, torch.float32), _stream()))
+    return out
+
+
+def refine_step(sched, x, eps, s_from, out=None):
+    import torch
+    sc = sched_config(sched)
+    batch = x.shape[0]
+    if out is None:
+        out = torch.empty_like(x)
+    _check(lib().drf_refine_step(C.byref(sc), _dev(x, torch.float32), _dev(eps, torch.float32), s_from, batch,
+                                 x.numel() // batch if batch else 0, _dev(out, torch.float32), _stream()))
+    return out
+
+
+class Denoiser:
+    """Owns a drf_denoiser handle."""
+
+    def __init__(self, dit, host_weights):
+        self.dit = dict(dit)
+        w = np.ascontiguousarray(host_weights, np.float32)
+        cfg = dit_config(dit)
+        h = C.c_void_p()
+        _check(lib().drf_denoiser_create(C.byref(cfg), w.ctypes.data_as(C.c_void_p), w.size, _stream(), C.byref(h)))
+        self.h = h
+
+    def close(self):
+        if getattr(self, "h", None):
+            lib().drf_denoiser_destroy(self.h)
+            self.h = None
+
+    __del__ = close
+
+    def reserve(self, max_slots):
+        _check(lib().drf_denoiser_reserve(self.h, max_slots))
+
+    def _cond_dtype(self):
+        import torch
+        return torch.int32 if self.dit["cond"] == COND_CLASS else torch.float32
+
+    def eps_batched(self, x, t, cond, out=None):
+        import torch
+        if out is None:
+            out = torch.empty_like(x)
+        _check(lib().drf_eps_batched(self.h, _dev(x, torch.float32), _dev(t, torch.int32),
+                                     _dev(cond, self._cond_dtype()), x.shape[0], _dev(out, torch.float32), _stream()))
+        return out
+
+    def eps_trace(self, x, t, cond, n_blocks):
+        import torch
+        d = self.dit
+        T = (d["lat_h"] // d["patch"]) * (d["lat_w"] // d["patch"])
+        out = torch.empty((x.shape[0], T, d["hidden"]), dtype=torch.float32, device=x.device)
+        _check(lib().drf_eps_trace(self.h, _dev(x, torch.float32), _dev(t, torch.int32),
+                                   _dev(cond, self._cond_dtype()), x.shape[0], n_blocks, _dev(out), _stream()))
+        return out
+
+    def sample(self, sched, mode, n, x_T, cond, null_cond=None, cfg_scale=0.0, out=None):
+        import torch
+        sc = sched_config(sched)
+        if out is None:
+            out = torch.empty_like(x_T)
+        _check(lib().drf_sample(self.h, C.byref(sc), mode, n, x_T.shape[0], _dev(x_T, torch.float32),
+                                _dev(cond, self._cond_dtype()), _dev(null_cond, self._cond_dtype()),
+                                float(cfg_scale or 0.0), _dev(out, torch.float32), _stream()))
+        return out
+
+    def profile_enable(self, on=True):
+        _check(lib().drf_profile_enable(self.h, 1 if on else 0))
+
+    def profile_read(self, which):
+        n, ms, work = C.c_longlong(0), C.c_double(0), C.c_double(0)
+        _check(lib().drf_profile_read(self.h, which, C.byref(n), C.byref(ms), C.byref(work)))
+        return dict(launches=n.value, ms=ms.value, work=work.value)

@@ -1,0 +1,100 @@
+"""Host-side checks that need no GPU: the library loads, exports every symbol the
+header declares, its plan table equals the oracle's bit for bit, and bad arguments
+come back as status codes."""
+import ctypes as C
+import os
+import re
+
+import numpy as np
+import pytest
+
+from paper_2603_25872_amd import drf, inputs as I
+
+ROOT = os.path.dirname(os.path.dirname(os.path.abspath(__file__)))
+
+
+def header_symbols():
+    text = open(os.path.join(ROOT, "include", "drf.h")).read()
+    text = re.sub(r"/\*.*?\*/", "", text, flags=re.S)
+    return sorted(set(re.findall(r"\b(drf_[a-z_0-9]+)\s*\(", text)))
+
+
+def test_library_exports_every_declared_symbol():
+    L = drf.lib()
+    names = header_symbols()
+    assert sorted(names) == sorted(drf.SYMBOLS)
+    for n in names:
+        assert getattr(L, n) is not None
+
+
+def sched(S):
+    return dict(train_steps=1000, beta_start=1e-4, beta_end=0.02, steps=S, eta=0.0)
+
+
+@pytest.mark.parametrize("mode", [drf.CONSERVATIVE, drf.AGGRESSIVE])
+@pytest.mark.parametrize("S", [1, 2, 3, 5, 20, 28, 30, 50, 1000])
+@pytest.mark.parametrize("n", [1, 2, 3, 4, 8, 9, 64, 100])
+def test_plan_table_bit_exact_with_oracle(orc, mode, S, n):
+    got = drf.plan_build(sched(S), mode, n)
+    want = orc.plan(sched(S), mode, n)
+    assert got.dtype == want.dtype == np.int32
+    assert got.shape == want.shape
+    assert np.array_equal(got, want)
+
+
+def test_plan_for_the_five_workloads(orc):
+    for idx, c in I.CONFIGS.items():
+        assert np.array_equal(drf.plan_build(c["sched"], c["mode"], c["n"]), orc.plan(c["sched"], c["mode"], c["n"]))
+
+
+def test_plan_capacity_is_respected():
+    sc = drf.sched_config(sched(20))
+    cnt = C.c_size_t(0)
+    rows = np.full((3, 5), -7, np.int32)
+    assert drf.lib().drf_plan_build(C.byref(sc), 0, 2, rows.ctypes.data_as(C.c_void_p), 2, C.byref(cnt)) == 0
+    assert cnt.value > 3
+    assert (rows[2] == -7).all() and (rows[:2] != -7).any()
+
+
+@pytest.mark.parametrize("bad", [dict(steps=0), dict(steps=1001), dict(eta=0.5), dict(beta_start=0.0),
+                                 dict(beta_end=1.0), dict(train_steps=1)])
+def test_bad_schedule_is_a_status_code(bad):
+    sc = drf.sched_config(dict(sched(20), **bad))
+    cnt = C.c_size_t(0)
+    st = drf.lib().drf_plan_build(C.byref(sc), 0, 2, None, 0, C.byref(cnt))
+    assert st in (-1, -5)
+    assert len(drf.lib().drf_last_error()) > 0
+    if "eta" in bad:
+        assert st == -5
+
+
+def test_bad_plan_arguments():
+    sc = drf.sched_config(sched(20))
+    cnt = C.c_size_t(0)
+    L = drf.lib()
+    assert L.drf_plan_build(C.byref(sc), 0, 0, None, 0, C.byref(cnt)) == -1
+    assert L.drf_plan_build(C.byref(sc), 5, 2, None, 0, C.byref(cnt)) == -1
+    assert L.drf_plan_build(None, 0, 2, None, 0, C.byref(cnt)) == -1
+    assert L.drf_plan_build(C.byref(sc), 0, 2, None, 0, None) == -1
+
+
+def test_weight_count_matches_layout_and_oracle(orc):
+    for idx, c in I.CONFIGS.items():
+        n = drf.denoiser_weight_count(c["dit"])
+        assert n == I.param_count(c["dit"]) == orc.weight_count(c["dit"])
+    assert drf.denoiser_weight_count(dict(I.CONFIGS[1]["dit"], hidden=130)) == 0       # not divisible by heads
+    assert drf.denoiser_weight_count(dict(I.CONFIGS[2]["dit"], hidden=390)) == 0       # bf16 needs % 64
+
+
+def test_null_handles_are_rejected_without_touching_the_gpu():
+    L = drf.lib()
+    assert L.drf_eps_batched(None, None, None, None, 1, None, None) == -1
+    assert L.drf_sample(None, None, 0, 1, 1, None, None, None, C.c_float(0), None, None) == -1
+    assert L.drf_denoiser_reserve(None, 4) == -1
+    L.drf_denoiser_destroy(None)
+    sc = drf.sched_config(sched(20))
+    to = (C.c_int * 1)(3)
+    # zero-sized work is a no-op, NULL buffers with real sizes are an error
+    assert L.drf_skip_transition(C.byref(sc), None, None, 5, to, 1, 0, 16, None, None) == 0
+    assert L.drf_skip_transition(C.byref(sc), None, None, 5, to, 1, 2, 16, None, None) == -1
+    assert L.drf_refine_step(C.byref(sc), None, None, 0, 1, 16, None, None) == -1
