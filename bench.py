@@ -1,0 +1,147 @@
+"""Throughput of the DRiffusion hot path on one MI355X.
+
+One "step" is one drf_sample call: the whole draft-and-refine loop (all S sampling
+steps: batched DiT passes + fused guidance/refine/draft updates) over one batch of
+synthetic latents, inputs resident in HBM.  Default workload: configuration 3
+(DiT-XL/2-shaped, bf16, guidance 4, 50-step DDIM, conservative n=4, batch 8).
+
+Prints ONE JSON line: eps-evals/s over the whole call, ms per step, the roofline of the
+dominant kernel family (bf16 MFMA GEMM) measured with HIP events on the library's
+stream during one extra instrumented call, and the CPU oracle timed on a bounded
+sample of the same workload (one slot evaluation of the same DiT)."""
+import argparse
+import json
+import os
+import sys
+import time
+
+ROOT = os.path.dirname(os.path.abspath(__file__))
+if ROOT not in sys.path:
+    sys.path.insert(0, ROOT)
+
+PEAK_BF16_TFLOPS = 2500.0     # MI355X dense bf16 MFMA
+PEAK_HBM_GBS = 8000.0
+
+
+def slot_eval_flops(dit):
+    """Algorithmic flops of one slot evaluation (2 M N K, unpadded head dim)."""
+    D, L, R = dit["hidden"], dit["depth"], dit["mlp_ratio"]
+    T = (dit["lat_h"] // dit["patch"]) * (dit["lat_w"] // dit["patch"])
+    P = dit["in_ch"] * dit["patch"] ** 2
+    per = 2 * T * D * (3 * D) + 2 * T * D * D + 2 * 2 * T * D * R * D + 4 * T * T * D
+    if dit["cond"] == 2:
+        per += 2 * 2 * T * D * D + 4 * T * dit["ctx_len"] * D
+    return L * per + 2 * 2 * T * D * P
+
+
+def main():
+    ap = argparse.ArgumentParser()
+    ap.add_argument("--gpus", type=int, default=1)
+    ap.add_argument("--steps", type=int, default=5)
+    ap.add_argument("--warmup", type=int, default=1)
+    ap.add_argument("--config", type=int, default=3, help="workload configuration 1..5")
+    ap.add_argument("--n", type=int, default=None, help="override the block size n")
+    ap.add_argument("--mode", type=int, default=None, help="0 conservative, 1 aggressive")
+    ap.add_argument("--no-cpu-baseline", action="store_true")
+    ap.add_argument("--no-roofline", action="store_true")
+    args = ap.parse_args()
+    if args.gpus != 1:
+        sys.exit("bench.py: this build runs on one GPU; the paper's n devices are n batch-slot groups of a "
+                 "single pass, so --gpus must be 1")
+
+    import numpy as np
+    import torch
+    from paper_2603_25872_amd import drf, inputs as I
+
+    cfg = I.config(args.config)
+    dit, sd = cfg["dit"], cfg["sched"]
+    n = cfg["n"] if args.n is None else args.n
+    mode = cfg["mode"] if args.mode is None else args.mode
+    B, S = cfg["batch"], sd["steps"]
+    g = 2 if cfg["guidance"] else 1
+    assert torch.cuda.is_available(), "bench.py needs a GPU"
+
+    w = I.weights(dit, args.config)
+    den = drf.Denoiser(dit, w)
+    den.reserve(n * g * B)
+    xT = torch.from_numpy(I.latent_noise(dit, B, args.config)).cuda()
+    cond = torch.from_numpy(I.conditioning(dit, B, args.config)).cuda()
+    null = torch.from_numpy(I.conditioning(dit, B, args.config, null=True)).cuda() if cfg["guidance"] else None
+    out = torch.empty_like(xT)
+
+    def step():
+        den.sample(sd, mode, n, xT, cond, null, cfg["guidance"] or 0.0, out=out)
+
+    for _ in range(args.warmup):
+        step()
+    torch.cuda.synchronize()
+    t0 = time.perf_counter()
+    for _ in range(args.steps):
+        step()
+    torch.cuda.synchronize()
+    dt = time.perf_counter() - t0
+    assert bool(torch.isfinite(out).all())
+
+    evals = S * B * g                                   # slot evaluations per call
+    ms_step = dt / args.steps * 1e3
+    flops_call = evals * slot_eval_flops(dit)
+    result = {
+        "metric": "draft eps-evals/sec (slot evaluations of the batched DiT pass over the whole drf_sample call)",
+        "value": evals * args.steps / dt,
+        "unit": "eps-evals/s",
+        "n_gpus": 1, "steps": args.steps, "warmup": args.warmup,
+        "ms_per_step": ms_step,
+        "ms_per_sample": ms_step / B,
+        "higher_is_better": True, "scaling": "weak", "vs_baseline": None,
+        "dtype": "bf16" if dit["dtype"] == I.BF16 else "f32",
+        "data": "synthetic",
+        "config": {"workload": "config %d: %s, %d-step DDIM, %s n=%d, batch %d, guidance %s" % (
+            args.config, cfg["name"], S, "aggressive" if mode else "conservative", n, B, cfg["guidance"]),
+            "slots_per_full_pass": n * g * B, "evals_per_step": evals},
+        "achieved_tflops_whole_call": flops_call / (ms_step * 1e-3) / 1e12,
+        "frac_of_bf16_mfma_peak_whole_call": flops_call / (ms_step * 1e-3) / 1e12 / PEAK_BF16_TFLOPS,
+    }
+
+    if not args.no_roofline:
+        # one more call with per-launch HIP events on the library's stream
+        den.profile_enable(True)
+        step()
+        fam = {k: den.profile_read(v) for k, v in (("gemm", drf.PROF_GEMM), ("attn", drf.PROF_ATTN),
+                                                    ("elementwise", drf.PROF_ELEMWISE), ("update", drf.PROF_UPDATE))}
+        den.profile_enable(False)
+        gm = fam["gemm"]
+        ach = gm["work"] / (gm["ms"] * 1e-3) / 1e12 if gm["ms"] > 0 else 0.0
+        result["roofline"] = {"bound": "mfma", "kernel": "gemm_bf16_kernel (all GEMM launches of one call)",
+                              "achieved": ach, "peak": PEAK_BF16_TFLOPS, "unit": "TFLOP/s",
+                              "frac": ach / PEAK_BF16_TFLOPS, "traffic": None,
+                              "launches": gm["launches"], "avg_launch_us": gm["ms"] * 1e3 / max(gm["launches"], 1),
+                              "flops_per_launch": gm["work"] / max(gm["launches"], 1)}
+        result["families_ms"] = {k: round(v["ms"], 3) for k, v in fam.items()}
+        at = fam["attn"]
+        if at["ms"] > 0:
+            result["attn_tflops"] = at["work"] / (at["ms"] * 1e-3) / 1e12
+        up = fam["update"]
+        if up["ms"] > 0:
+            result["update_kernel"] = {"launches": up["launches"], "avg_launch_us": up["ms"] * 1e3 / up["launches"],
+                                       "achieved_GBps": up["work"] / (up["ms"] * 1e-3) / 1e9}
+    den.close()
+
+    if not args.no_cpu_baseline:
+        # the oracle as it stands, on a bounded sample: one slot evaluation of the same DiT
+        from oracle.ref import Oracle
+        orc = Oracle(64)
+        wd = orc.prepare_weights(w)
+        x1 = I.latent_noise(dit, 1, args.config)
+        c1 = I.conditioning(dit, 1, args.config)
+        t1 = np.array([500], np.int32)
+        t0 = time.perf_counter()
+        orc.dit_eps(dit, wd, x1, t1, c1)
+        ct = time.perf_counter() - t0
+        result["cpu_baseline"] = {"value": 1.0 / ct, "unit": "eps-evals/s", "cores": orc.threads(), "kind": "oracle",
+                                  "sample": "1 slot evaluation of the same DiT (fp64 oracle, %.1f s); a full call is %d of them"
+                                            % (ct, evals)}
+    print(json.dumps(result))
+
+
+if __name__ == "__main__":
+    main()

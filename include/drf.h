@@ -211,6 +211,15 @@ enum { DRF_PROF_GEMM = 0, DRF_PROF_ATTN = 1, DRF_PROF_ELEMWISE = 2, DRF_PROF_UPD
 drf_status drf_profile_enable(drf_denoiser* den, int on);
 drf_status drf_profile_read(drf_denoiser* den, int which, long long* launches, double* ms, double* work);
 
+/*
+ * Measurement hook: one launch of the library's bf16 GEMM on caller buffers,
+ * out[M][N] (bf16) = A[M][K] (bf16) . W[N][K]^T (bf16) + bias[N] (fp32), all DEVICE.
+ * variant 0 = the tile shape the forward pass would pick, > 0 forces one (for sweeps).
+ * K % 64 == 0 and N % 4 == 0 are required.
+ */
+drf_status drf_probe_gemm_bf16(const void* A, const void* W, int M, int N, int K, void* out_bf16, const float* bias,
+                               int variant, void* hip_stream);
+
 /* HOST, thread-local, valid until the next failing call on this thread. */
 const char* drf_last_error(void);
 

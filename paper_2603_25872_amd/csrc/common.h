@@ -81,7 +81,10 @@ struct Epilogue {
     const float* bias;      // [N]
     const float* gate;      // EPI_RESID: gate[(m / rows_per_slot) * gate_ld + n], NULL = ungated
     int gate_ld, rows_per_slot;
+    uint32_t rps_magic; int rps_shift;   // m / rows_per_slot == fast_div(m, rps_magic, rps_shift), see set_rows_per_slot
 };
+// Fills rows_per_slot and its division constants (exact for 0 <= m < 2^31).
+void set_rows_per_slot(Epilogue* e, int rows_per_slot);
 // C[M][N] = A[M][K] . W[N][K]^T, then the epilogue.  bf16: K % 64 == 0.
 drf_status launch_gemm_bf16(const bf16_t* A, const bf16_t* W, int M, int N, int K, const Epilogue& e, hipStream_t st);
 drf_status launch_gemm_f32(const float* A, const float* W, int M, int N, int K, const Epilogue& e, hipStream_t st);
@@ -105,6 +108,7 @@ struct CondArgs {
     int D, slots;
     SlotMap map;
     float* act_f32; bf16_t* act_bf16;
+    float* scratch;          // slots * (256 + 3 D) floats
 };
 drf_status launch_cond_embed(const CondArgs& a, hipStream_t st);
 

@@ -44,7 +44,7 @@ struct drf_denoiser {
     float* pos = nullptr;           // [T][D]
     // workspace
     int cap_slots = 0;
-    float *resid = nullptr, *mod = nullptr, *cact32 = nullptr;
+    float *resid = nullptr, *mod = nullptr, *cact32 = nullptr, *cscratch = nullptr;
     void *hbuf = nullptr, *qkv = nullptr, *mid = nullptr, *cact = nullptr;
     // cross-attention K/V cache [L][rows][ctx_len][2D] and its staging
     void* xkv = nullptr; void* ctx_act = nullptr; int cap_ctx_rows = 0;
@@ -148,7 +148,7 @@ drf_status ensure_workspace(drf_denoiser* d, int slots, hipStream_t st)
 {
     if (slots <= d->cap_slots) return DRF_OK;
     DRF_HIP(hipStreamSynchronize(st));
-    void* olds[] = { d->resid, d->mod, d->cact32, d->hbuf, d->qkv, d->mid, d->cact };
+    void* olds[] = { d->resid, d->mod, d->cact32, d->cscratch, d->hbuf, d->qkv, d->mid, d->cact };
     for (void* p : olds) dev_free(d, p);
     d->cap_slots = 0;
     const size_t M = (size_t)slots * d->dm.T, D = (size_t)d->dm.D, act = d->bf16 ? 2 : 4;
@@ -156,6 +156,7 @@ drf_status ensure_workspace(drf_denoiser* d, int slots, hipStream_t st)
     if ((rc = dev_alloc(d, (void**)&d->resid, M * D * 4)) != DRF_OK) return rc;
     if ((rc = dev_alloc(d, (void**)&d->mod, (size_t)slots * d->n_mod * 4)) != DRF_OK) return rc;
     if ((rc = dev_alloc(d, (void**)&d->cact32, (size_t)slots * D * 4)) != DRF_OK) return rc;
+    if ((rc = dev_alloc(d, (void**)&d->cscratch, (size_t)slots * (kTFreq + 3 * D) * 4)) != DRF_OK) return rc;
     if ((rc = dev_alloc(d, &d->cact, (size_t)slots * D * act)) != DRF_OK) return rc;
     if ((rc = dev_alloc(d, &d->hbuf, M * D * act)) != DRF_OK) return rc;
     if ((rc = dev_alloc(d, &d->qkv, M * 3 * D * act)) != DRF_OK) return rc;
@@ -197,7 +198,7 @@ Epilogue epi_resid(float* resid, int ldo, const float* gate, int gate_ld, int ro
 {
     Epilogue e{};
     e.mode = EPI_RESID; e.out = resid; e.ldo = ldo; e.out_f32 = 1; e.gate = gate; e.gate_ld = gate_ld;
-    e.rows_per_slot = rows_per_slot;
+    set_rows_per_slot(&e, rows_per_slot);
     return e;
 }
 
@@ -235,6 +236,7 @@ drf_status forward(drf_denoiser* d, const float* x, const SlotMap& map, const vo
         ca.t_w1 = d->t_w1; ca.t_b1 = d->t_b1; ca.t_w2 = d->t_w2; ca.t_b2 = d->t_b2; ca.c_w = d->c_w; ca.c_b = d->c_b;
         ca.table = d->table; ca.cond = cond; ca.cond_kind = d->cfg.cond; ca.cond_dim = d->cfg.cond_dim; ca.D = D;
         ca.slots = slots; ca.map = map; ca.act_f32 = d->cact32; ca.act_bf16 = d->bf16 ? (bf16_t*)d->cact : nullptr;
+        ca.scratch = d->cscratch;
         {
             ProfScope ps(d, st, DRF_PROF_ELEMWISE, 4.0 * slots * ((double)kTFreq * D + (double)D * D));
             if ((rc = launch_cond_embed(ca, st)) != DRF_OK) return rc;
@@ -585,4 +587,18 @@ extern "C" drf_status drf_profile_read(drf_denoiser* den, int which, long long* 
     p.recs.swap(keep);
     if (p.recs.empty()) p.used = 0;
     return DRF_OK;
+}
+
+namespace drf { extern int g_gemm_variant; }
+
+extern "C" drf_status drf_probe_gemm_bf16(const void* A, const void* W, int M, int N, int K, void* out_bf16,
+                                          const float* bias, int variant, void* hip_stream)
+{
+    if (!A || !W || !out_bf16 || !bias || M < 0 || N < 0 || K < 0) DRF_FAIL(DRF_EINVAL, "bad argument");
+    Epilogue e{};
+    e.mode = EPI_STORE; e.out = out_bf16; e.ldo = N; e.out_f32 = 0; e.bias = bias;
+    drf::g_gemm_variant = variant;
+    drf_status rc = launch_gemm_bf16((const bf16_t*)A, (const bf16_t*)W, M, N, K, e, (hipStream_t)hip_stream);
+    drf::g_gemm_variant = 0;
+    return rc;
 }

@@ -9,11 +9,24 @@ namespace {
 constexpr int kWave = 64;
 constexpr int kTFreq = 256;
 
+// Sum over the 64 lanes with DPP adds (no LDS traffic): inclusive scan inside each row of 16
+// lanes (row_shr 1, 2, 4, 8 with zero fill), then the row totals are passed on with
+// row_bcast:15 (into rows 1 and 3) and row_bcast:31 (into rows 2 and 3); lane 63 ends with
+// the wave total, which readlane hands to every lane.
+template <int CTRL, int ROW_MASK>
+__device__ inline float dpp_add(float v)
+{
+    return v + __int_as_float(__builtin_amdgcn_update_dpp(0, __float_as_int(v), CTRL, ROW_MASK, 0xf, true));
+}
 __device__ inline float wave_sum(float v)
 {
-#pragma unroll
-    for (int o = 32; o > 0; o >>= 1) v += __shfl_xor(v, o, kWave);
-    return v;
+    v = dpp_add<0x111, 0xf>(v);
+    v = dpp_add<0x112, 0xf>(v);
+    v = dpp_add<0x114, 0xf>(v);
+    v = dpp_add<0x118, 0xf>(v);
+    v = dpp_add<0x142, 0xa>(v);
+    v = dpp_add<0x143, 0xc>(v);
+    return __int_as_float(__builtin_amdgcn_readlane(__float_as_int(v), 63));
 }
 
 __device__ inline float silu(float v) { return v / (1.f + __expf(-v)); }
@@ -22,58 +35,73 @@ __device__ inline int slot_tau(const SlotMap& m, int slot) { return m.t_dev ? m.
 __device__ inline int slot_xrow(const SlotMap& m, int slot) { return (slot / m.x_group) * m.x_batch + slot % m.x_batch; }
 __device__ inline int slot_crow(const SlotMap& m, int slot) { return m.cond_mod ? slot % m.cond_mod : slot; }
 
-// One block per slot.  femb(tau) -> Linear -> SiLU -> Linear (+ cond embedding) -> SiLU.
-// Each wave owns output rows; lanes stride over the input so weight reads coalesce.
-__global__ void __launch_bounds__(256) cond_embed_kernel(const CondArgs a)
+// Conditioning front-end, four small launches that each fill the chip:
+//   femb(tau) per slot -> skinny Linear + SiLU -> skinny Linear -> add cond embedding, SiLU.
+
+// femb[slot][256] = [cos(tau f_i) | sin(tau f_i)], f_i = 10000^(-i/128).  Double precision:
+// tau * f reaches ~1e3 rad, beyond what fp32 range reduction keeps to 1e-7.
+__global__ void __launch_bounds__(kTFreq / 2) time_features_kernel(const SlotMap map, int slots, float* __restrict__ femb)
 {
-    extern __shared__ float sm[];          // femb[256] | h1[D] | cvec (vector cond) [cond_dim]
-    float* femb = sm;
-    float* h1 = sm + kTFreq;
-    float* cv = h1 + a.D;
-    const int slot = blockIdx.x, tid = threadIdx.x, lane = tid & 63, wave = tid >> 6, nw = blockDim.x >> 6;
-    const int tau = slot_tau(a.map, slot);
-    // sinusoid in double: tau * f reaches ~1e3 rad, beyond what fp32 range reduction keeps to 1e-7
-    if (tid < kTFreq / 2) {
-        double f = exp(-9.210340371976184 * (double)tid / (double)(kTFreq / 2));
-        double ang = (double)tau * f;
-        femb[tid] = (float)cos(ang);
-        femb[kTFreq / 2 + tid] = (float)sin(ang);
+    const int slot = blockIdx.x, i = threadIdx.x;
+    if (slot >= slots) return;
+    const double f = exp(-9.210340371976184 * (double)i / (double)(kTFreq / 2));
+    const double ang = (double)slot_tau(map, slot) * f;
+    femb[(size_t)slot * kTFreq + i] = (float)cos(ang);
+    femb[(size_t)slot * kTFreq + kTFreq / 2 + i] = (float)sin(ang);
+}
+
+// y[r][j] = act(sum_k x[row(r)][k] w[j][k] + b[j]) for a handful of rows r (one per slot).
+// One wave per output column j keeps its weight row in registers and sweeps the rows;
+// lanes stride over k so both operands are read coalesced.  K <= 64 * kSkinnyPer.
+constexpr int kSkinnyPer = 32;
+template <bool SILU>
+__global__ void __launch_bounds__(256) skinny_linear_kernel(const float* __restrict__ x, int ldx, int row_mod,
+                                                            const float* __restrict__ w, const float* __restrict__ b,
+                                                            int rows, int K, int N, float* __restrict__ y)
+{
+    const int lane = threadIdx.x & 63, j = blockIdx.x * (blockDim.x >> 6) + (threadIdx.x >> 6);
+    if (j >= N) return;
+    float wr[kSkinnyPer];
+#pragma unroll
+    for (int i = 0; i < kSkinnyPer; ++i) {
+        const int k = i * kWave + lane;
+        wr[i] = k < K ? w[(size_t)j * K + k] : 0.f;
     }
-    const int crow = slot_crow(a.map, slot);
-    if (a.cond_kind == DRF_COND_VECTOR)
-        for (int i = tid; i < a.cond_dim; i += blockDim.x) cv[i] = ((const float*)a.cond)[(size_t)crow * a.cond_dim + i];
-    __syncthreads();
-    for (int j = wave; j < a.D; j += nw) {
-        const float* wr = a.t_w1 + (size_t)j * kTFreq;
+    const float bj = b[j];
+    const int per = (K + kWave - 1) / kWave;
+    for (int r = 0; r < rows; ++r) {
+        const float* xr = x + (size_t)(row_mod ? r % row_mod : r) * ldx;
         float acc = 0.f;
-        for (int k = lane; k < kTFreq; k += kWave) acc = fmaf(femb[k], wr[k], acc);
-        acc = wave_sum(acc);
-        if (lane == 0) h1[j] = silu(acc + a.t_b1[j]);
-    }
-    __syncthreads();
-    int cls = 0;
-    if (a.cond_kind == DRF_COND_CLASS) {
-        cls = ((const int32_t*)a.cond)[crow];
-        if (cls < 0 || cls > a.cond_dim) cls = a.cond_dim;
-    }
-    for (int j = wave; j < a.D; j += nw) {
-        const float* wr = a.t_w2 + (size_t)j * a.D;
-        float acc = 0.f;
-        for (int k = lane; k < a.D; k += kWave) acc = fmaf(h1[k], wr[k], acc);
-        if (a.cond_kind == DRF_COND_VECTOR) {
-            const float* cr = a.c_w + (size_t)j * a.cond_dim;
-            for (int k = lane; k < a.cond_dim; k += kWave) acc = fmaf(cv[k], cr[k], acc);
+#pragma unroll
+        for (int i = 0; i < kSkinnyPer; ++i) {
+            if (i < per) {
+                const int k = i * kWave + lane;
+                acc = fmaf(k < K ? xr[k] : 0.f, wr[i], acc);
+            }
         }
-        acc = wave_sum(acc);
-        if (lane == 0) {
-            float c = acc + a.t_b2[j];
-            if (a.cond_kind == DRF_COND_VECTOR) c += a.c_b[j];
-            else if (a.cond_kind == DRF_COND_CLASS) c += a.table[(size_t)cls * a.D + j];
-            float s = silu(c);
-            a.act_f32[(size_t)slot * a.D + j] = s;
-            if (a.act_bf16) a.act_bf16[(size_t)slot * a.D + j] = (bf16_t)s;
-        }
+        acc = wave_sum(acc) + bj;
+        if (lane == 0) y[(size_t)r * N + j] = SILU ? silu(acc) : acc;
     }
+}
+
+// c = t_emb + cond embedding; writes SiLU(c) as float and, if asked, bf16.
+__global__ void __launch_bounds__(256) cond_finish_kernel(const float* __restrict__ temb, const float* __restrict__ vemb,
+                                                          const float* __restrict__ table, const int32_t* __restrict__ cls,
+                                                          const SlotMap map, int n_classes, int slots, int D,
+                                                          float* __restrict__ act_f32, bf16_t* __restrict__ act_bf16)
+{
+    const int slot = blockIdx.y, j = blockIdx.x * blockDim.x + threadIdx.x;
+    if (slot >= slots || j >= D) return;
+    float c = temb[(size_t)slot * D + j];
+    if (vemb) c += vemb[(size_t)slot * D + j];
+    if (table) {
+        int k = cls[slot_crow(map, slot)];
+        if (k < 0 || k > n_classes) k = n_classes;
+        c += table[(size_t)k * D + j];
+    }
+    const float s = silu(c);
+    act_f32[(size_t)slot * D + j] = s;
+    if (act_bf16) act_bf16[(size_t)slot * D + j] = (bf16_t)s;
 }
 
 // resid[m][j] = sum_k token[m][k] w[j][k] + b[j] + pos[token][j].  One block per kTok tokens.
@@ -117,92 +145,128 @@ __global__ void __launch_bounds__(256) patch_embed_kernel(const float* __restric
 }
 
 // One wave per row; the row stays in registers between the statistics and the output.
-constexpr int kLnMaxPer = 32;              // hidden <= 64 * 32
-template <typename OutT>
+// Lanes hold pairs of adjacent columns (8-byte loads, 4- or 8-byte stores); PER pairs per lane.
+template <typename OutT> struct Pair;
+template <> struct Pair<float> { typedef float2 type; };
+template <> struct Pair<bf16_t> { typedef bf16_t type __attribute__((ext_vector_type(2))); };
+
+template <int PER, typename OutT>
 __global__ void __launch_bounds__(256) ln_modulate_kernel(const float* __restrict__ resid, const float* __restrict__ shift,
                                                           const float* __restrict__ scale, int mod_ld, int rows_per_slot,
                                                           int M, int D, OutT* __restrict__ out)
 {
+    typedef typename Pair<OutT>::type out2;
     const int lane = threadIdx.x & 63, row = blockIdx.x * (blockDim.x >> 6) + (threadIdx.x >> 6);
     if (row >= M) return;
-    const float* xr = resid + (size_t)row * D;
-    float v[kLnMaxPer];
+    const int D2 = D >> 1;
+    const float2* xr = reinterpret_cast<const float2*>(resid + (size_t)row * D);
+    float2 v[PER];
     float sum = 0.f;
 #pragma unroll
-    for (int i = 0; i < kLnMaxPer; ++i) {
+    for (int i = 0; i < PER; ++i) {
         const int j = i * kWave + lane;
-        v[i] = j < D ? xr[j] : 0.f;
-        sum += v[i];
+        v[i] = j < D2 ? xr[j] : make_float2(0.f, 0.f);
+        sum += v[i].x + v[i].y;
     }
     const float mean = wave_sum(sum) / (float)D;
     float sq = 0.f;
 #pragma unroll
-    for (int i = 0; i < kLnMaxPer; ++i) {
+    for (int i = 0; i < PER; ++i) {
         const int j = i * kWave + lane;
-        const float dlt = j < D ? v[i] - mean : 0.f;
-        sq = fmaf(dlt, dlt, sq);
+        const float dx = j < D2 ? v[i].x - mean : 0.f, dy = j < D2 ? v[i].y - mean : 0.f;
+        sq = fmaf(dx, dx, fmaf(dy, dy, sq));
     }
     const float rstd = rsqrtf(wave_sum(sq) / (float)D + 1e-6f);
     const size_t mrow = (size_t)(row / rows_per_slot) * mod_ld;
+    const float2* sh = shift ? reinterpret_cast<const float2*>(shift + mrow) : nullptr;
+    const float2* sc = shift ? reinterpret_cast<const float2*>(scale + mrow) : nullptr;
+    out2* orow = reinterpret_cast<out2*>(out + (size_t)row * D);
 #pragma unroll
-    for (int i = 0; i < kLnMaxPer; ++i) {
+    for (int i = 0; i < PER; ++i) {
         const int j = i * kWave + lane;
-        if (j < D) {
-            float y = (v[i] - mean) * rstd;
-            if (shift) y = fmaf(y, 1.f + scale[mrow + j], shift[mrow + j]);
-            out[(size_t)row * D + j] = (OutT)y;
+        if (j < D2) {
+            float y0 = (v[i].x - mean) * rstd, y1 = (v[i].y - mean) * rstd;
+            if (sh) {
+                const float2 s2 = sc[j], h2 = sh[j];
+                y0 = fmaf(y0, 1.f + s2.x, h2.x);
+                y1 = fmaf(y1, 1.f + s2.y, h2.y);
+            }
+            out2 o;
+            o.x = (OutT)y0; o.y = (OutT)y1;
+            orow[j] = o;
         }
     }
 }
 
-// Final layer: LN + modulate, Linear(D -> P), scatter to [C][H][W].  One wave per token.
+// Final layer: LN + modulate, Linear(D -> P), scatter to [C][H][W].  The projection matrix
+// is staged in LDS once per block; each wave then handles rows in turn, keeping P partial
+// sums per lane and reducing them across the wave at the end.
+constexpr int kFinalRowsPerBlock = 64;
+constexpr int kFinalMaxP = 16;
+template <int PER>
 __global__ void __launch_bounds__(256) final_kernel(const float* __restrict__ resid, const float* __restrict__ shift,
                                                     const float* __restrict__ scale, int mod_ld,
                                                     const float* __restrict__ w, const float* __restrict__ b,
                                                     const DitDims dm, int M, float* __restrict__ eps_out)
 {
-    const int lane = threadIdx.x & 63, row = blockIdx.x * (blockDim.x >> 6) + (threadIdx.x >> 6);
-    if (row >= M) return;
-    const int D = dm.D;
-    const float* xr = resid + (size_t)row * D;
-    float v[kLnMaxPer];
-    float sum = 0.f;
-#pragma unroll
-    for (int i = 0; i < kLnMaxPer; ++i) {
-        const int j = i * kWave + lane;
-        v[i] = j < D ? xr[j] : 0.f;
-        sum += v[i];
-    }
-    const float mean = wave_sum(sum) / (float)D;
-    float sq = 0.f;
-#pragma unroll
-    for (int i = 0; i < kLnMaxPer; ++i) {
-        const int j = i * kWave + lane;
-        const float dlt = j < D ? v[i] - mean : 0.f;
-        sq = fmaf(dlt, dlt, sq);
-    }
-    const float rstd = rsqrtf(wave_sum(sq) / (float)D + 1e-6f);
-    const int slot = row / dm.T, t = row % dm.T, py = t / dm.gw, px = t % dm.gw;
-    const size_t mrow = (size_t)slot * mod_ld;
-#pragma unroll
-    for (int i = 0; i < kLnMaxPer; ++i) {
-        const int j = i * kWave + lane;
-        v[i] = j < D ? fmaf((v[i] - mean) * rstd, 1.f + scale[mrow + j], shift[mrow + j]) : 0.f;
-    }
+    extern __shared__ float sw[];          // [P][D]
+    const int D = dm.D, P = dm.P;
+    for (int i = threadIdx.x; i < P * D; i += blockDim.x) sw[i] = w[i];
+    __syncthreads();
+    const int lane = threadIdx.x & 63, wave = threadIdx.x >> 6, nw = blockDim.x >> 6;
     const size_t E = (size_t)dm.C * dm.H * dm.W;
     const int pp = dm.patch * dm.patch;
-    for (int k = 0; k < dm.P; ++k) {
-        const float* wr = w + (size_t)k * D;
-        float acc = 0.f;
+    const int row_end = min(M, (int)(blockIdx.x + 1) * kFinalRowsPerBlock);
+    for (int row = blockIdx.x * kFinalRowsPerBlock + wave; row < row_end; row += nw) {
+        const float* xr = resid + (size_t)row * D;
+        float v[PER];
+        float sum = 0.f;
 #pragma unroll
-        for (int i = 0; i < kLnMaxPer; ++i) {
+        for (int i = 0; i < PER; ++i) {
             const int j = i * kWave + lane;
-            if (j < D) acc = fmaf(v[i], wr[j], acc);
+            v[i] = j < D ? xr[j] : 0.f;
+            sum += v[i];
         }
-        acc = wave_sum(acc);
-        if (lane == 0) {
-            const int ch = k / pp, dy = (k % pp) / dm.patch, dx = k % dm.patch;
-            eps_out[(size_t)slot * E + ((size_t)ch * dm.H + py * dm.patch + dy) * dm.W + px * dm.patch + dx] = acc + b[k];
+        const float mean = wave_sum(sum) / (float)D;
+        float sq = 0.f;
+#pragma unroll
+        for (int i = 0; i < PER; ++i) {
+            const int j = i * kWave + lane;
+            const float dlt = j < D ? v[i] - mean : 0.f;
+            sq = fmaf(dlt, dlt, sq);
+        }
+        const float rstd = rsqrtf(wave_sum(sq) / (float)D + 1e-6f);
+        const int slot = row / dm.T, t = row % dm.T, py = t / dm.gw, px = t % dm.gw;
+        const size_t mrow = (size_t)slot * mod_ld;
+#pragma unroll
+        for (int i = 0; i < PER; ++i) {
+            const int j = i * kWave + lane;
+            v[i] = j < D ? fmaf((v[i] - mean) * rstd, 1.f + scale[mrow + j], shift[mrow + j]) : 0.f;
+        }
+        for (int k0 = 0; k0 < P; k0 += kFinalMaxP) {
+            float acc[kFinalMaxP];
+#pragma unroll
+            for (int k = 0; k < kFinalMaxP; ++k) {
+                acc[k] = 0.f;
+                if (k0 + k < P) {
+#pragma unroll
+                    for (int i = 0; i < PER; ++i) {
+                        const int j = i * kWave + lane;
+                        if (j < D) acc[k] = fmaf(v[i], sw[(k0 + k) * D + j], acc[k]);
+                    }
+                }
+            }
+#pragma unroll
+            for (int k = 0; k < kFinalMaxP; ++k) acc[k] = wave_sum(acc[k]);
+            // lane k writes output k
+            float mine = 0.f;
+#pragma unroll
+            for (int k = 0; k < kFinalMaxP; ++k) mine = lane == k ? acc[k] : mine;
+            const int k = k0 + lane;
+            if (lane < kFinalMaxP && k < P) {
+                const int ch = k / pp, dy = (k % pp) / dm.patch, dx = k % dm.patch;
+                eps_out[(size_t)slot * E + ((size_t)ch * dm.H + py * dm.patch + dy) * dm.W + px * dm.patch + dx] = mine + b[k];
+            }
         }
     }
 }
@@ -218,8 +282,26 @@ __global__ void f32_to_bf16_kernel(const float* __restrict__ in, bf16_t* __restr
 drf_status launch_cond_embed(const CondArgs& a, hipStream_t st)
 {
     if (a.slots == 0) return DRF_OK;
-    const size_t smem = sizeof(float) * (size_t)(kTFreq + a.D + (a.cond_kind == DRF_COND_VECTOR ? a.cond_dim : 0));
-    hipLaunchKernelGGL(cond_embed_kernel, dim3(a.slots), dim3(256), smem, st, a);
+    const int D = a.D, S = a.slots;
+    if (D > kWave * kSkinnyPer || (a.cond_kind == DRF_COND_VECTOR && a.cond_dim > kWave * kSkinnyPer))
+        DRF_FAIL(DRF_ESHAPE, "conditioning front-end needs hidden and cond_dim <= %d", kWave * kSkinnyPer);
+    // scratch rows: femb [S][256] | h1 [S][D] | temb [S][D] | vemb [S][D]
+    float* femb = a.scratch;
+    float* h1 = femb + (size_t)S * kTFreq;
+    float* temb = h1 + (size_t)S * D;
+    float* vemb = temb + (size_t)S * D;
+    const dim3 gcol((D + 3) / 4);
+    hipLaunchKernelGGL(time_features_kernel, dim3(S), dim3(kTFreq / 2), 0, st, a.map, S, femb);
+    hipLaunchKernelGGL(skinny_linear_kernel<true>, gcol, dim3(256), 0, st, femb, kTFreq, 0, a.t_w1, a.t_b1, S, kTFreq, D, h1);
+    hipLaunchKernelGGL(skinny_linear_kernel<false>, gcol, dim3(256), 0, st, h1, D, 0, a.t_w2, a.t_b2, S, D, D, temb);
+    const bool vec = a.cond_kind == DRF_COND_VECTOR;
+    if (vec)
+        hipLaunchKernelGGL(skinny_linear_kernel<false>, gcol, dim3(256), 0, st, (const float*)a.cond, a.cond_dim,
+                           a.map.cond_mod, a.c_w, a.c_b, S, a.cond_dim, D, vemb);
+    const bool cls = a.cond_kind == DRF_COND_CLASS;
+    hipLaunchKernelGGL(cond_finish_kernel, dim3((D + 255) / 256, S), dim3(256), 0, st, temb, vec ? vemb : nullptr,
+                       cls ? a.table : nullptr, cls ? (const int32_t*)a.cond : nullptr, a.map, a.cond_dim, S, D,
+                       a.act_f32, a.act_bf16);
     DRF_HIP(hipGetLastError());
     return DRF_OK;
 }
@@ -235,18 +317,30 @@ drf_status launch_patch_embed(const float* x, const SlotMap& map, const float* w
     return DRF_OK;
 }
 
+template <int PER>
+static void launch_ln_inst(const float* resid, const float* shift, const float* scale, int mod_ld, int rows_per_slot, int M,
+                           int D, void* out, int out_f32, hipStream_t st)
+{
+    const dim3 grid((M + 3) / 4), block(256);
+    if (out_f32)
+        hipLaunchKernelGGL((ln_modulate_kernel<PER, float>), grid, block, 0, st, resid, shift, scale, mod_ld, rows_per_slot, M,
+                           D, (float*)out);
+    else
+        hipLaunchKernelGGL((ln_modulate_kernel<PER, bf16_t>), grid, block, 0, st, resid, shift, scale, mod_ld, rows_per_slot,
+                           M, D, (bf16_t*)out);
+}
+
 drf_status launch_ln_modulate(const float* resid, const float* shift, const float* scale, int mod_ld, int rows_per_slot,
                               int M, int D, void* out, int out_f32, hipStream_t st)
 {
     if (M == 0) return DRF_OK;
-    if (D > kWave * kLnMaxPer) DRF_FAIL(DRF_ESHAPE, "hidden %d exceeds LayerNorm kernel limit %d", D, kWave * kLnMaxPer);
-    const dim3 grid((M + 3) / 4), block(256);
-    if (out_f32)
-        hipLaunchKernelGGL(ln_modulate_kernel<float>, grid, block, 0, st, resid, shift, scale, mod_ld, rows_per_slot, M, D,
-                           (float*)out);
-    else
-        hipLaunchKernelGGL(ln_modulate_kernel<bf16_t>, grid, block, 0, st, resid, shift, scale, mod_ld, rows_per_slot, M, D,
-                           (bf16_t*)out);
+    if (D > 2048 || D % 2 != 0 || mod_ld % 2 != 0) DRF_FAIL(DRF_ESHAPE, "LayerNorm kernel needs even hidden <= 2048 (got %d)", D);
+    const int per = (D / 2 + kWave - 1) / kWave;      // column pairs per lane
+    if (per <= 1) launch_ln_inst<1>(resid, shift, scale, mod_ld, rows_per_slot, M, D, out, out_f32, st);
+    else if (per <= 3) launch_ln_inst<3>(resid, shift, scale, mod_ld, rows_per_slot, M, D, out, out_f32, st);
+    else if (per <= 5) launch_ln_inst<5>(resid, shift, scale, mod_ld, rows_per_slot, M, D, out, out_f32, st);
+    else if (per <= 9) launch_ln_inst<9>(resid, shift, scale, mod_ld, rows_per_slot, M, D, out, out_f32, st);
+    else launch_ln_inst<16>(resid, shift, scale, mod_ld, rows_per_slot, M, D, out, out_f32, st);
     DRF_HIP(hipGetLastError());
     return DRF_OK;
 }
@@ -256,7 +350,20 @@ drf_status launch_final(const float* resid, const float* shift, const float* sca
 {
     const int M = slots * dm.T;
     if (M == 0) return DRF_OK;
-    hipLaunchKernelGGL(final_kernel, dim3((M + 3) / 4), dim3(256), 0, st, resid, shift, scale, mod_ld, w, b, dm, M, eps_out);
+    const size_t smem = sizeof(float) * (size_t)dm.P * dm.D;
+    if (dm.D > 2048 || smem > 150 * 1024) DRF_FAIL(DRF_ESHAPE, "final layer needs hidden <= 2048 and patch dim * hidden * 4 <= 150 KiB");
+    const dim3 grid((M + kFinalRowsPerBlock - 1) / kFinalRowsPerBlock), block(256);
+    const int per = (dm.D + kWave - 1) / kWave;
+    static bool attr_set = false;
+    if (!attr_set) {
+        DRF_HIP(hipFuncSetAttribute(reinterpret_cast<const void*>(final_kernel<6>), hipFuncAttributeMaxDynamicSharedMemorySize, 150 * 1024));
+        DRF_HIP(hipFuncSetAttribute(reinterpret_cast<const void*>(final_kernel<18>), hipFuncAttributeMaxDynamicSharedMemorySize, 150 * 1024));
+        DRF_HIP(hipFuncSetAttribute(reinterpret_cast<const void*>(final_kernel<32>), hipFuncAttributeMaxDynamicSharedMemorySize, 150 * 1024));
+        attr_set = true;
+    }
+    if (per <= 6) hipLaunchKernelGGL(final_kernel<6>, grid, block, smem, st, resid, shift, scale, mod_ld, w, b, dm, M, eps_out);
+    else if (per <= 18) hipLaunchKernelGGL(final_kernel<18>, grid, block, smem, st, resid, shift, scale, mod_ld, w, b, dm, M, eps_out);
+    else hipLaunchKernelGGL(final_kernel<32>, grid, block, smem, st, resid, shift, scale, mod_ld, w, b, dm, M, eps_out);
     DRF_HIP(hipGetLastError());
     return DRF_OK;
 }

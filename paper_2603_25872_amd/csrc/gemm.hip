@@ -11,12 +11,19 @@ typedef bf16_t bf16x8 __attribute__((ext_vector_type(8)));
 typedef bf16_t bf16x4 __attribute__((ext_vector_type(4)));
 typedef float f32x16 __attribute__((ext_vector_type(16)));
 
+// GELU (tanh form): 0.5 x (1 + tanh(u)) = x * sigmoid(2u), u = sqrt(2/pi) (x + 0.044715 x^3).
+// One exp2 and one reciprocal (both hardware transcendental ops, ~1 ulp).
 __device__ inline float gelu_tanh(float x)
 {
-    const float u = 0.7978845608028654f * (x + 0.044715f * x * x * x);
-    // tanh(u) = 1 - 2 / (exp(2u) + 1)
-    const float t = 1.f - 2.f / (__expf(2.f * u) + 1.f);
-    return 0.5f * x * (1.f + t);
+    const float t = x * x;
+    const float m2u_log2e = x * fmaf(t, -0.1029432f, -2.3022082f);   // -2 u log2(e)
+    return x * __builtin_amdgcn_rcpf(1.f + __builtin_amdgcn_exp2f(m2u_log2e));
+}
+
+// floor(n / d) for 0 <= n < 2^31 with a host-made magic number (d >= 1).
+__device__ inline int fast_div(int n, uint32_t magic, int shift)
+{
+    return magic ? (int)(__umulhi((uint32_t)n, magic) >> shift) : (n >> shift);
 }
 
 // Applies the epilogue to 4 consecutive columns n..n+3 of row m (n % 4 == 0, n + 3 < N).
@@ -28,7 +35,7 @@ __device__ inline void epilogue4(const Epilogue& e, int m, int n, float v0, floa
         float4* xp = reinterpret_cast<float4*>((float*)e.out + (size_t)m * e.ldo + n);
         float4 x = *xp;
         if (e.gate) {
-            const float4 g = *reinterpret_cast<const float4*>(e.gate + (size_t)(m / e.rows_per_slot) * e.gate_ld + n);
+            const float4 g = *reinterpret_cast<const float4*>(e.gate + (size_t)fast_div(m, e.rps_magic, e.rps_shift) * e.gate_ld + n);
             x.x = fmaf(g.x, v0, x.x); x.y = fmaf(g.y, v1, x.y); x.z = fmaf(g.z, v2, x.z); x.w = fmaf(g.w, v3, x.w);
         } else {
             x.x += v0; x.y += v1; x.z += v2; x.w += v3;
@@ -143,6 +150,207 @@ gemm_bf16_kernel(const bf16_t* __restrict__ A, const bf16_t* __restrict__ W, int
     }
 }
 
+#define DRF_GLOBAL_AS __attribute__((address_space(1)))
+#define DRF_LDS_AS __attribute__((address_space(3)))
+template <int N> __device__ inline void wait_vmcnt() { asm volatile("s_waitcnt vmcnt(%0)" ::"n"(N) : "memory"); }
+
+// ------------------------------------------------ bf16 MFMA 16x16x32, wide tiles
+// The main kernel for the DiT's big GEMMs.  BM x BN x 64 block tile (256 x 288 for hidden
+// 1152: 1152, 3456 and 4608 are all multiples of 288, so at 64 row tiles every GEMM of the
+// block is a whole number of 256-tile rounds), 8 waves as WM x WN, wave tile (BM/WM) x
+// (BN/WN) built from 16x16x32 MFMAs so that widths only need to be multiples of 16.
+//  - operands go HBM -> LDS directly (global_load_lds_dwordx4: every lane supplies its own
+//    global address and the wave's 64 x 16 bytes land contiguously in LDS), two stages, so
+//    the copy of k-tile t+1 overlaps the MFMAs of k-tile t.  A tile row is 128 bytes = 8
+//    chunks; chunk c of row r sits at position c ^ ((r / 2) % 8), which keeps both the DMA
+//    writes and the ds_read_b128 operand fetches free of bank conflicts;
+//  - workgroup ids are remapped so that each XCD (ids are dealt round-robin over the 8 XCDs)
+//    works on a compact group of tiles and shares A/W slices through its own L2;
+//  - the weight tile is the MFMA A operand: a lane ends with 4 consecutive columns n of one
+//    row m per accumulator;
+//  - epilogue: each wave transposes its accumulators through its own slice of the (now
+//    idle) LDS stages and then touches global memory in whole rows: 16 bytes per lane,
+//    consecutive lanes on consecutive addresses.
+typedef float f32x4 __attribute__((ext_vector_type(4)));
+
+template <int BM, int BN, int BK, int NS, int WM, int WN>
+__global__ void __launch_bounds__(WM * WN * 64)
+gemm_bf16_xl_kernel(const bf16_t* __restrict__ A, const bf16_t* __restrict__ W, int M, int N, int K, const Epilogue e,
+                    int tiles_m, int tiles_n, int dbg)
+{
+    constexpr int NW = WM * WN, TM = BM / WM, TN = BN / WN, MI = TM / 16, NI = TN / 16, KS = BK / 32;
+    constexpr int CPR = BK / 8, RPI = 64 / CPR, RB = 256 / (BK * 2);
+    constexpr int SEG = (BM + BN) / RPI, LPT = (SEG + NW - 1) / NW;
+    constexpr int STAGE = (BM + BN) * BK;
+    constexpr int GROUP_M = 8;
+    static_assert(TM % 16 == 0 && TN % 16 == 0 && (BM + BN) % RPI == 0 && BM % 16 == 0, "tile shape");
+    extern __shared__ __attribute__((aligned(16))) unsigned char smem_raw[];
+    bf16_t* smem = reinterpret_cast<bf16_t*>(smem_raw);
+
+    const int nb = tiles_m * tiles_n, b = blockIdx.x;
+    const int xcd = b & 7, local = b >> 3, q = nb >> 3, rem = nb & 7;
+    const int idx = xcd * q + (xcd < rem ? xcd : rem) + local;
+    const int per_group = GROUP_M * tiles_n, group = idx / per_group, first_m = group * GROUP_M;
+    const int gsz = tiles_m - first_m < GROUP_M ? tiles_m - first_m : GROUP_M;
+    const int tm = first_m + (idx % per_group) % gsz, tn = (idx % per_group) / gsz;
+    const int m0 = tm * BM, n0 = tn * BN;
+
+    const int tid = threadIdx.x, lane = tid & 63, wave = tid >> 6;
+    const int wm = wave % WM, wn = wave / WM;
+    const int l16 = lane & 15, quarter = lane >> 4;
+
+    // DMA: the A rows and W rows of a stage form one row space [0, BM + BN); a wave-wide
+    // instruction covers RPI rows.  Every wave issues LPT instructions; when SEG is not a
+    // multiple of the wave count the surplus ones repeat the last segment (same bytes, same place).
+    const int prow = lane / CPR, ppos = lane % CPR;
+    const bf16_t* src[LPT];
+    int dst[LPT];
+#pragma unroll
+    for (int i = 0; i < LPT; ++i) {
+        int g = wave * LPT + i; g = g < SEG ? g : SEG - 1;
+        const int r = g * RPI + prow;
+        const int chunk = ppos ^ ((r / RB) & (CPR - 1));
+        if (r < BM) {
+            int gm = m0 + r; gm = gm < M ? gm : M - 1;
+            src[i] = A + (size_t)gm * K + chunk * 8;
+        } else {
+            int gn = n0 + r - BM; gn = gn < N ? gn : N - 1;
+            src[i] = W + (size_t)gn * K + chunk * 8;
+        }
+        dst[i] = g * RPI * BK;
+    }
+    auto issue = [&](int kt, int stage) {
+        if ((dbg == 1 || dbg == 4) && kt >= NS) return;             // timing experiment: no steady-state loads
+#pragma unroll
+        for (int i = 0; i < LPT; ++i)
+            __builtin_amdgcn_global_load_lds((const DRF_GLOBAL_AS void*)(src[i] + kt * BK),
+                                             (DRF_LDS_AS void*)(smem + stage * STAGE + dst[i]), 16, 0, 0);
+    };
+
+    f32x4 acc[NI][MI];
+#pragma unroll
+    for (int i = 0; i < NI; ++i)
+#pragma unroll
+        for (int j = 0; j < MI; ++j) acc[i][j] = (f32x4){ 0.f, 0.f, 0.f, 0.f };
+
+    int koff[KS];
+#pragma unroll
+    for (int ks = 0; ks < KS; ++ks) koff[ks] = l16 * BK + (((ks * 4 + quarter) ^ ((l16 / RB) & (CPR - 1))) << 3);
+
+    const int nk = K / BK;
+#pragma unroll
+    for (int s = 0; s < NS - 1; ++s)
+        if (s < nk) issue(s, s);
+    for (int kt = 0; kt < nk; ++kt) {
+        const int stage = kt % NS;
+        // tile kt has landed once only the NS-2 younger tiles remain in flight
+        if (kt + NS - 2 < nk) wait_vmcnt<LPT * (NS - 2)>(); else wait_vmcnt<0>();
+        __syncthreads();                     // ... for every wave, and all are done reading tile kt-1's stage
+        if (kt + NS - 1 < nk) issue(kt + NS - 1, (kt + NS - 1) % NS);
+        const bf16_t* pa = smem + stage * STAGE + wm * TM * BK;
+        const bf16_t* pw = smem + stage * STAGE + BM * BK + wn * TN * BK;
+#pragma unroll
+        for (int ks = 0; ks < KS; ++ks) {
+            bf16x8 fa[MI], fw[NI];
+#pragma unroll
+            for (int j = 0; j < MI; ++j) fa[j] = *reinterpret_cast<const bf16x8*>(pa + j * 16 * BK + koff[ks]);
+#pragma unroll
+            for (int i = 0; i < NI; ++i) fw[i] = *reinterpret_cast<const bf16x8*>(pw + i * 16 * BK + koff[ks]);
+            __builtin_amdgcn_s_setprio(1);
+#pragma unroll
+            for (int i = 0; i < NI; ++i)
+#pragma unroll
+                for (int j = 0; j < MI; ++j)
+                    acc[i][j] = __builtin_amdgcn_mfma_f32_16x16x32_bf16(fw[i], fa[j], acc[i][j], 0, 0, 0);
+            __builtin_amdgcn_s_setprio(0);
+        }
+    }
+    if (dbg >= 3 && acc[0][0][0] != 12345.678f) return;             // timing experiment: no epilogue
+
+    // ---- epilogue through LDS: acc[i][j][r] is (m = j*16 + l16, n = i*16 + 4*quarter + r) of the wave tile
+    __syncthreads();
+    constexpr int WBYTES = NS * STAGE * 2 / NW;                     // this wave's private slice of the stages
+    unsigned char* wbuf = smem_raw + wave * WBYTES;
+    const int mw = m0 + wm * TM, nw = n0 + wn * TN;
+    const bool resid = e.mode == EPI_RESID;
+    if (resid || e.out_f32) {
+        constexpr int ROWB = TN * 4 + ((TN * 4) % 128 == 0 ? 16 : 0);
+        constexpr int RPP = (WBYTES / ROWB) / 16 * 16 < TM ? (WBYTES / ROWB) / 16 * 16 : TM;   // rows per pass
+        static_assert(RPP >= 16, "LDS slice too small for the fp32 epilogue");
+        constexpr int CH = TN / 4;                                  // float4 chunks per row
+#pragma unroll
+        for (int j0 = 0; j0 < MI; j0 += RPP / 16) {
+#pragma unroll
+            for (int jj = 0; jj < RPP / 16; ++jj) {
+                const int j = j0 + jj;
+                if (j < MI) {
+#pragma unroll
+                    for (int i = 0; i < NI; ++i) {
+                        const int n = nw + i * 16 + 4 * quarter;
+                        const int nc = n < N ? n : 0;
+                        const float4 bb = *reinterpret_cast<const float4*>(e.bias + nc);
+                        float4 v = make_float4(acc[i][j][0] + bb.x, acc[i][j][1] + bb.y, acc[i][j][2] + bb.z, acc[i][j][3] + bb.w);
+                        if (e.mode == EPI_STORE_GELU) { v.x = gelu_tanh(v.x); v.y = gelu_tanh(v.y); v.z = gelu_tanh(v.z); v.w = gelu_tanh(v.w); }
+                        *reinterpret_cast<float4*>(wbuf + (jj * 16 + l16) * ROWB + (i * 16 + 4 * quarter) * 4) = v;
+                    }
+                }
+            }
+            // rows back out, CH float4 chunks each
+            for (int id = lane; id < RPP * CH; id += 64) {
+                const int rl = id / CH, c = id % CH;
+                const int m = mw + j0 * 16 + rl, n = nw + c * 4;
+                if (j0 * 16 + rl < TM && m < M && n < N) {
+                    const float4 v = *reinterpret_cast<const float4*>(wbuf + rl * ROWB + c * 16);
+                    float4* xp = reinterpret_cast<float4*>((float*)e.out + (size_t)m * e.ldo + n);
+                    if (resid) {
+                        float4 x = *xp;
+                        if (e.gate) {
+                            const float4 g = *reinterpret_cast<const float4*>(e.gate + (size_t)fast_div(m, e.rps_magic, e.rps_shift) * e.gate_ld + n);
+                            x.x = fmaf(g.x, v.x, x.x); x.y = fmaf(g.y, v.y, x.y); x.z = fmaf(g.z, v.z, x.z); x.w = fmaf(g.w, v.w, x.w);
+                        } else {
+                            x.x += v.x; x.y += v.y; x.z += v.z; x.w += v.w;
+                        }
+                        *xp = x;
+                    } else {
+                        *xp = v;
+                    }
+                }
+            }
+        }
+    } else {
+        constexpr int ROWB = TN * 2 + ((TN * 2) % 128 == 0 ? 16 : 0);
+        constexpr int RPP = (WBYTES / ROWB) / 16 * 16 < TM ? (WBYTES / ROWB) / 16 * 16 : TM;
+        static_assert(RPP >= 16, "LDS slice too small for the bf16 epilogue");
+        constexpr int CH = TN / 8;                                  // 16-byte chunks per row
+#pragma unroll
+        for (int j0 = 0; j0 < MI; j0 += RPP / 16) {
+#pragma unroll
+            for (int jj = 0; jj < RPP / 16; ++jj) {
+                const int j = j0 + jj;
+                if (j < MI) {
+#pragma unroll
+                    for (int i = 0; i < NI; ++i) {
+                        const int n = nw + i * 16 + 4 * quarter;
+                        const int nc = n < N ? n : 0;
+                        const float4 bb = *reinterpret_cast<const float4*>(e.bias + nc);
+                        float v0 = acc[i][j][0] + bb.x, v1 = acc[i][j][1] + bb.y, v2 = acc[i][j][2] + bb.z, v3 = acc[i][j][3] + bb.w;
+                        if (e.mode == EPI_STORE_GELU) { v0 = gelu_tanh(v0); v1 = gelu_tanh(v1); v2 = gelu_tanh(v2); v3 = gelu_tanh(v3); }
+                        bf16x4 o = { (bf16_t)v0, (bf16_t)v1, (bf16_t)v2, (bf16_t)v3 };
+                        *reinterpret_cast<bf16x4*>(wbuf + (jj * 16 + l16) * ROWB + (i * 16 + 4 * quarter) * 2) = o;
+                    }
+                }
+            }
+            for (int id = lane; id < RPP * CH; id += 64) {
+                const int rl = id / CH, c = id % CH;
+                const int m = mw + j0 * 16 + rl, n = nw + c * 8;
+                if (j0 * 16 + rl < TM && m < M && n < N)
+                    *reinterpret_cast<bf16x8*>((bf16_t*)e.out + (size_t)m * e.ldo + n) =
+                        *reinterpret_cast<const bf16x8*>(wbuf + rl * ROWB + c * 16);
+            }
+        }
+    }
+}
+
 // ------------------------------------------------------------------------ fp32
 // 64 x 64 x 16 tile, 256 threads, 4 x 4 outputs per thread (columns n consecutive).
 __global__ void __launch_bounds__(256)
@@ -195,13 +403,64 @@ drf_status launch_bf16_tile(const bf16_t* A, const bf16_t* W, int M, int N, int 
     return DRF_OK;
 }
 
+int g_gemm_debug = 0;   // timing experiments only (results are wrong when non-zero)
+
+template <int BM, int BN, int BK, int NS, int WM, int WN>
+drf_status launch_bf16_xl(const bf16_t* A, const bf16_t* W, int M, int N, int K, const Epilogue& e, hipStream_t st)
+{
+    constexpr size_t smem = (size_t)NS * (BM + BN) * BK * sizeof(bf16_t);
+    static bool attr_set = false;
+    auto kern = gemm_bf16_xl_kernel<BM, BN, BK, NS, WM, WN>;
+    if (!attr_set) {
+        DRF_HIP(hipFuncSetAttribute(reinterpret_cast<const void*>(kern), hipFuncAttributeMaxDynamicSharedMemorySize, (int)smem));
+        attr_set = true;
+    }
+    const int tiles_m = (M + BM - 1) / BM, tiles_n = (N + BN - 1) / BN;
+    hipLaunchKernelGGL(kern, dim3(tiles_m * tiles_n), dim3(WM * WN * 64), smem, st, A, W, M, N, K, e, tiles_m, tiles_n,
+                       g_gemm_debug);
+    DRF_HIP(hipGetLastError());
+    return DRF_OK;
+}
+
 }  // namespace
+
+int g_gemm_variant = 0;   // measurement hook: 0 = heuristic, else force a tile shape
 
 drf_status launch_gemm_bf16(const bf16_t* A, const bf16_t* W, int M, int N, int K, const Epilogue& e, hipStream_t st)
 {
     if (M == 0 || N == 0) return DRF_OK;
     if (K % 64 != 0 || N % 4 != 0 || e.ldo % 4 != 0) DRF_FAIL(DRF_ESHAPE, "bf16 GEMM needs K %% 64 == 0 and N %% 4 == 0 (M=%d N=%d K=%d)", M, N, K);
-    return launch_bf16_tile<128, 128, 2, 2>(A, W, M, N, K, e, st);
+    if ((size_t)M * K >= ((size_t)1 << 31) || (size_t)N * K >= ((size_t)1 << 31))
+        DRF_FAIL(DRF_ESHAPE, "bf16 GEMM operand exceeds 2^31 elements");
+    int v = g_gemm_variant;
+    g_gemm_debug = v / 100;
+    v %= 100;
+    if (v == 0) {
+        // Pick the tile shape that wastes the least MFMA work: padding of the last tile row /
+        // column, and the idle CUs of the last round of 256 concurrent tiles.
+        struct Cand { int id, bm, bn; double eff; };
+        const Cand cands[] = { { 2, 256, 288, 1.0 }, { 3, 256, 256, 0.97 }, { 4, 128, 288, 0.8 }, { 7, 128, 144, 0.6 },
+                               { 5, 128, 128, 0.55 } };
+        double best = 0.0;
+        v = 1;
+        if (M >= 512) {
+            for (const Cand& c : cands) {
+                const double tm = (M + c.bm - 1) / c.bm, tn = (N + c.bn - 1) / c.bn, tiles = tm * tn;
+                const double rounds = (double)((long long)(tiles + 255) / 256);
+                const double score = c.eff * ((double)M * N) / (rounds * 256.0 * c.bm * c.bn);
+                if (score > best) { best = score; v = c.id; }
+            }
+        }
+    }
+    switch (v) {
+    case 2: return launch_bf16_xl<256, 288, 64, 2, 4, 3>(A, W, M, N, K, e, st);
+    case 3: return launch_bf16_xl<256, 256, 64, 2, 4, 2>(A, W, M, N, K, e, st);
+    case 4: return launch_bf16_xl<128, 288, 64, 2, 2, 2>(A, W, M, N, K, e, st);
+    case 5: return launch_bf16_xl<128, 128, 64, 2, 2, 2>(A, W, M, N, K, e, st);
+    case 6: return launch_bf16_xl<256, 288, 64, 2, 4, 2>(A, W, M, N, K, e, st);
+    case 7: return launch_bf16_xl<128, 144, 64, 2, 4, 1>(A, W, M, N, K, e, st);
+    default: return launch_bf16_tile<128, 128, 2, 2>(A, W, M, N, K, e, st);
+    }
 }
 
 drf_status launch_gemm_f32(const float* A, const float* W, int M, int N, int K, const Epilogue& e, hipStream_t st)

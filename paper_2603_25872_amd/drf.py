@@ -19,7 +19,7 @@ PROF_GEMM, PROF_ATTN, PROF_ELEMWISE, PROF_UPDATE = 0, 1, 2, 3
 
 SYMBOLS = ["drf_denoiser_weight_count", "drf_denoiser_create", "drf_denoiser_destroy", "drf_denoiser_reserve",
            "drf_eps_batched", "drf_eps_trace", "drf_skip_transition", "drf_refine_step", "drf_sample",
-           "drf_plan_build", "drf_profile_enable", "drf_profile_read", "drf_last_error"]
+           "drf_plan_build", "drf_profile_enable", "drf_profile_read", "drf_probe_gemm_bf16", "drf_last_error"]
 
 
 class DitConfig(C.Structure):
@@ -66,6 +66,8 @@ def lib():
         L.drf_plan_build.argtypes = [C.c_void_p, C.c_int, C.c_int, C.c_void_p, C.c_size_t, C.c_void_p]
         L.drf_profile_enable.argtypes = [C.c_void_p, C.c_int]
         L.drf_profile_read.argtypes = [C.c_void_p, C.c_int, C.c_void_p, C.c_void_p, C.c_void_p]
+        L.drf_probe_gemm_bf16.argtypes = [C.c_void_p, C.c_void_p, C.c_int, C.c_int, C.c_int, C.c_void_p, C.c_void_p,
+                                          C.c_int, C.c_void_p]
         L.drf_last_error.restype = C.c_char_p
         _lib = L
     return _lib
@@ -139,6 +141,18 @@ def refine_step(sched, x, eps, s_from, out=None):
         out = torch.empty_like(x)
     _check(lib().drf_refine_step(C.byref(sc), _dev(x, torch.float32), _dev(eps, torch.float32), s_from, batch,
                                  x.numel() // batch if batch else 0, _dev(out, torch.float32), _stream()))
+    return out
+
+
+def probe_gemm_bf16(A, W, bias, out=None, variant=0):
+    """out[M,N] = A[M,K] @ W[N,K]^T + bias with the library's bf16 GEMM (measurement hook)."""
+    import torch
+    M, K = A.shape
+    N = W.shape[0]
+    if out is None:
+        out = torch.empty((M, N), dtype=torch.bfloat16, device=A.device)
+    _check(lib().drf_probe_gemm_bf16(_dev(A, torch.bfloat16), _dev(W, torch.bfloat16), M, N, K,
+                                     _dev(out, torch.bfloat16), _dev(bias, torch.float32), variant, _stream()))
     return out
 
 
