@@ -51,36 +51,46 @@ __global__ void __launch_bounds__(kTFreq / 2) time_features_kernel(const SlotMap
 }
 
 // y[r][j] = act(sum_k x[row(r)][k] w[j][k] + b[j]) for a handful of rows r (one per slot).
-// One wave per output column j keeps its weight row in registers and sweeps the rows;
-// lanes stride over k so both operands are read coalesced.  K <= 64 * kSkinnyPer.
-constexpr int kSkinnyPer = 32;
+// A block owns kSkinnyCols output columns for up to 64 rows at a time and walks K in chunks
+// staged through LDS: thread (row, column pair) accumulates two outputs.
+constexpr int kSkinnyCols = 8, kSkinnyChunk = 128;
 template <bool SILU>
 __global__ void __launch_bounds__(256) skinny_linear_kernel(const float* __restrict__ x, int ldx, int row_mod,
                                                             const float* __restrict__ w, const float* __restrict__ b,
                                                             int rows, int K, int N, float* __restrict__ y)
 {
-    const int lane = threadIdx.x & 63, j = blockIdx.x * (blockDim.x >> 6) + (threadIdx.x >> 6);
-    if (j >= N) return;
-    float wr[kSkinnyPer];
-#pragma unroll
-    for (int i = 0; i < kSkinnyPer; ++i) {
-        const int k = i * kWave + lane;
-        wr[i] = k < K ? w[(size_t)j * K + k] : 0.f;
-    }
-    const float bj = b[j];
-    const int per = (K + kWave - 1) / kWave;
-    for (int r = 0; r < rows; ++r) {
-        const float* xr = x + (size_t)(row_mod ? r % row_mod : r) * ldx;
-        float acc = 0.f;
-#pragma unroll
-        for (int i = 0; i < kSkinnyPer; ++i) {
-            if (i < per) {
-                const int k = i * kWave + lane;
-                acc = fmaf(k < K ? xr[k] : 0.f, wr[i], acc);
+    __shared__ float xs[64][kSkinnyChunk + 1];
+    __shared__ float ws[kSkinnyCols][kSkinnyChunk + 1];
+    const int tid = threadIdx.x, rl = tid & 63, cg = tid >> 6;
+    const int j0 = blockIdx.x * kSkinnyCols;
+    for (int r0 = 0; r0 < rows; r0 += 64) {
+        float acc0 = 0.f, acc1 = 0.f;
+        for (int k0 = 0; k0 < K; k0 += kSkinnyChunk) {
+            __syncthreads();
+            for (int i = tid; i < 64 * kSkinnyChunk; i += 256) {
+                const int r = i / kSkinnyChunk, k = i % kSkinnyChunk, rr = r0 + r;
+                float v = 0.f;
+                if (rr < rows && k0 + k < K) v = x[(size_t)(row_mod ? rr % row_mod : rr) * ldx + k0 + k];
+                xs[r][k] = v;
+            }
+            for (int i = tid; i < kSkinnyCols * kSkinnyChunk; i += 256) {
+                const int c = i / kSkinnyChunk, k = i % kSkinnyChunk;
+                ws[c][k] = (j0 + c < N && k0 + k < K) ? w[(size_t)(j0 + c) * K + k0 + k] : 0.f;
+            }
+            __syncthreads();
+#pragma unroll 8
+            for (int k = 0; k < kSkinnyChunk; ++k) {
+                const float xv = xs[rl][k];
+                acc0 = fmaf(xv, ws[2 * cg][k], acc0);
+                acc1 = fmaf(xv, ws[2 * cg + 1][k], acc1);
             }
         }
-        acc = wave_sum(acc) + bj;
-        if (lane == 0) y[(size_t)r * N + j] = SILU ? silu(acc) : acc;
+        const int r = r0 + rl;
+        if (r < rows) {
+            const int ja = j0 + 2 * cg, jb = ja + 1;
+            if (ja < N) { const float v = acc0 + b[ja]; y[(size_t)r * N + ja] = SILU ? silu(v) : v; }
+            if (jb < N) { const float v = acc1 + b[jb]; y[(size_t)r * N + jb] = SILU ? silu(v) : v; }
+        }
     }
 }
 
@@ -198,74 +208,70 @@ __global__ void __launch_bounds__(256) ln_modulate_kernel(const float* __restric
     }
 }
 
-// Final layer: LN + modulate, Linear(D -> P), scatter to [C][H][W].  The projection matrix
-// is staged in LDS once per block; each wave then handles rows in turn, keeping P partial
-// sums per lane and reducing them across the wave at the end.
+// Final layer: LN + modulate, Linear(D -> P), scatter to [C][H][W].  A block of 4 waves takes
+// kFinalRowsPerBlock token rows; wave w keeps the weights of outputs w, w+4, w+8, w+12 (of each
+// group of 16) in registers and sweeps the rows, so nothing but the residual rows is re-read.
 constexpr int kFinalRowsPerBlock = 64;
-constexpr int kFinalMaxP = 16;
 template <int PER>
 __global__ void __launch_bounds__(256) final_kernel(const float* __restrict__ resid, const float* __restrict__ shift,
                                                     const float* __restrict__ scale, int mod_ld,
                                                     const float* __restrict__ w, const float* __restrict__ b,
                                                     const DitDims dm, int M, float* __restrict__ eps_out)
 {
-    extern __shared__ float sw[];          // [P][D]
     const int D = dm.D, P = dm.P;
-    for (int i = threadIdx.x; i < P * D; i += blockDim.x) sw[i] = w[i];
-    __syncthreads();
-    const int lane = threadIdx.x & 63, wave = threadIdx.x >> 6, nw = blockDim.x >> 6;
+    const int lane = threadIdx.x & 63, wave = threadIdx.x >> 6;
     const size_t E = (size_t)dm.C * dm.H * dm.W;
     const int pp = dm.patch * dm.patch;
-    const int row_end = min(M, (int)(blockIdx.x + 1) * kFinalRowsPerBlock);
-    for (int row = blockIdx.x * kFinalRowsPerBlock + wave; row < row_end; row += nw) {
-        const float* xr = resid + (size_t)row * D;
-        float v[PER];
-        float sum = 0.f;
+    const int row0 = blockIdx.x * kFinalRowsPerBlock, row_end = min(M, row0 + kFinalRowsPerBlock);
+    for (int kbase = 0; kbase < P; kbase += 16) {
+        float wr[4][PER], bias[4];
 #pragma unroll
-        for (int i = 0; i < PER; ++i) {
-            const int j = i * kWave + lane;
-            v[i] = j < D ? xr[j] : 0.f;
-            sum += v[i];
+        for (int q = 0; q < 4; ++q) {
+            const int k = kbase + wave + 4 * q;
+            bias[q] = k < P ? b[k] : 0.f;
+#pragma unroll
+            for (int i = 0; i < PER; ++i) {
+                const int j = i * kWave + lane;
+                wr[q][i] = (k < P && j < D) ? w[(size_t)k * D + j] : 0.f;
+            }
         }
-        const float mean = wave_sum(sum) / (float)D;
-        float sq = 0.f;
+        for (int row = row0; row < row_end; ++row) {
+            const float* xr = resid + (size_t)row * D;
+            float v[PER];
+            float sum = 0.f;
 #pragma unroll
-        for (int i = 0; i < PER; ++i) {
-            const int j = i * kWave + lane;
-            const float dlt = j < D ? v[i] - mean : 0.f;
-            sq = fmaf(dlt, dlt, sq);
-        }
-        const float rstd = rsqrtf(wave_sum(sq) / (float)D + 1e-6f);
-        const int slot = row / dm.T, t = row % dm.T, py = t / dm.gw, px = t % dm.gw;
-        const size_t mrow = (size_t)slot * mod_ld;
+            for (int i = 0; i < PER; ++i) {
+                const int j = i * kWave + lane;
+                v[i] = j < D ? xr[j] : 0.f;
+                sum += v[i];
+            }
+            const float mean = wave_sum(sum) / (float)D;
+            float sq = 0.f;
 #pragma unroll
-        for (int i = 0; i < PER; ++i) {
-            const int j = i * kWave + lane;
-            v[i] = j < D ? fmaf((v[i] - mean) * rstd, 1.f + scale[mrow + j], shift[mrow + j]) : 0.f;
-        }
-        for (int k0 = 0; k0 < P; k0 += kFinalMaxP) {
-            float acc[kFinalMaxP];
+            for (int i = 0; i < PER; ++i) {
+                const int j = i * kWave + lane;
+                const float dlt = j < D ? v[i] - mean : 0.f;
+                sq = fmaf(dlt, dlt, sq);
+            }
+            const float rstd = rsqrtf(wave_sum(sq) / (float)D + 1e-6f);
+            const int slot = row / dm.T, t = row % dm.T, py = t / dm.gw, px = t % dm.gw;
+            const size_t mrow = (size_t)slot * mod_ld;
+            float acc[4] = { 0.f, 0.f, 0.f, 0.f };
 #pragma unroll
-            for (int k = 0; k < kFinalMaxP; ++k) {
-                acc[k] = 0.f;
-                if (k0 + k < P) {
+            for (int i = 0; i < PER; ++i) {
+                const int j = i * kWave + lane;
+                const float y = j < D ? fmaf((v[i] - mean) * rstd, 1.f + scale[mrow + j], shift[mrow + j]) : 0.f;
 #pragma unroll
-                    for (int i = 0; i < PER; ++i) {
-                        const int j = i * kWave + lane;
-                        if (j < D) acc[k] = fmaf(v[i], sw[(k0 + k) * D + j], acc[k]);
-                    }
-                }
+                for (int q = 0; q < 4; ++q) acc[q] = fmaf(y, wr[q][i], acc[q]);
             }
 #pragma unroll
-            for (int k = 0; k < kFinalMaxP; ++k) acc[k] = wave_sum(acc[k]);
-            // lane k writes output k
-            float mine = 0.f;
-#pragma unroll
-            for (int k = 0; k < kFinalMaxP; ++k) mine = lane == k ? acc[k] : mine;
-            const int k = k0 + lane;
-            if (lane < kFinalMaxP && k < P) {
-                const int ch = k / pp, dy = (k % pp) / dm.patch, dx = k % dm.patch;
-                eps_out[(size_t)slot * E + ((size_t)ch * dm.H + py * dm.patch + dy) * dm.W + px * dm.patch + dx] = mine + b[k];
+            for (int q = 0; q < 4; ++q) {
+                const float tot = wave_sum(acc[q]);
+                const int k = kbase + wave + 4 * q;
+                if (lane == 0 && k < P) {
+                    const int ch = k / pp, dy = (k % pp) / dm.patch, dx = k % dm.patch;
+                    eps_out[(size_t)slot * E + ((size_t)ch * dm.H + py * dm.patch + dy) * dm.W + px * dm.patch + dx] = tot + bias[q];
+                }
             }
         }
     }
@@ -283,14 +289,12 @@ drf_status launch_cond_embed(const CondArgs& a, hipStream_t st)
 {
     if (a.slots == 0) return DRF_OK;
     const int D = a.D, S = a.slots;
-    if (D > kWave * kSkinnyPer || (a.cond_kind == DRF_COND_VECTOR && a.cond_dim > kWave * kSkinnyPer))
-        DRF_FAIL(DRF_ESHAPE, "conditioning front-end needs hidden and cond_dim <= %d", kWave * kSkinnyPer);
     // scratch rows: femb [S][256] | h1 [S][D] | temb [S][D] | vemb [S][D]
     float* femb = a.scratch;
     float* h1 = femb + (size_t)S * kTFreq;
     float* temb = h1 + (size_t)S * D;
     float* vemb = temb + (size_t)S * D;
-    const dim3 gcol((D + 3) / 4);
+    const dim3 gcol((D + kSkinnyCols - 1) / kSkinnyCols);
     hipLaunchKernelGGL(time_features_kernel, dim3(S), dim3(kTFreq / 2), 0, st, a.map, S, femb);
     hipLaunchKernelGGL(skinny_linear_kernel<true>, gcol, dim3(256), 0, st, femb, kTFreq, 0, a.t_w1, a.t_b1, S, kTFreq, D, h1);
     hipLaunchKernelGGL(skinny_linear_kernel<false>, gcol, dim3(256), 0, st, h1, D, 0, a.t_w2, a.t_b2, S, D, D, temb);
@@ -350,20 +354,12 @@ drf_status launch_final(const float* resid, const float* shift, const float* sca
 {
     const int M = slots * dm.T;
     if (M == 0) return DRF_OK;
-    const size_t smem = sizeof(float) * (size_t)dm.P * dm.D;
-    if (dm.D > 2048 || smem > 150 * 1024) DRF_FAIL(DRF_ESHAPE, "final layer needs hidden <= 2048 and patch dim * hidden * 4 <= 150 KiB");
+    if (dm.D > 2048) DRF_FAIL(DRF_ESHAPE, "final layer needs hidden <= 2048");
     const dim3 grid((M + kFinalRowsPerBlock - 1) / kFinalRowsPerBlock), block(256);
     const int per = (dm.D + kWave - 1) / kWave;
-    static bool attr_set = false;
-    if (!attr_set) {
-        DRF_HIP(hipFuncSetAttribute(reinterpret_cast<const void*>(final_kernel<6>), hipFuncAttributeMaxDynamicSharedMemorySize, 150 * 1024));
-        DRF_HIP(hipFuncSetAttribute(reinterpret_cast<const void*>(final_kernel<18>), hipFuncAttributeMaxDynamicSharedMemorySize, 150 * 1024));
-        DRF_HIP(hipFuncSetAttribute(reinterpret_cast<const void*>(final_kernel<32>), hipFuncAttributeMaxDynamicSharedMemorySize, 150 * 1024));
-        attr_set = true;
-    }
-    if (per <= 6) hipLaunchKernelGGL(final_kernel<6>, grid, block, smem, st, resid, shift, scale, mod_ld, w, b, dm, M, eps_out);
-    else if (per <= 18) hipLaunchKernelGGL(final_kernel<18>, grid, block, smem, st, resid, shift, scale, mod_ld, w, b, dm, M, eps_out);
-    else hipLaunchKernelGGL(final_kernel<32>, grid, block, smem, st, resid, shift, scale, mod_ld, w, b, dm, M, eps_out);
+    if (per <= 6) hipLaunchKernelGGL(final_kernel<6>, grid, block, 0, st, resid, shift, scale, mod_ld, w, b, dm, M, eps_out);
+    else if (per <= 18) hipLaunchKernelGGL(final_kernel<18>, grid, block, 0, st, resid, shift, scale, mod_ld, w, b, dm, M, eps_out);
+    else hipLaunchKernelGGL(final_kernel<32>, grid, block, 0, st, resid, shift, scale, mod_ld, w, b, dm, M, eps_out);
     DRF_HIP(hipGetLastError());
     return DRF_OK;
 }
