@@ -220,6 +220,13 @@ drf_status drf_profile_read(drf_denoiser* den, int which, long long* launches, d
 drf_status drf_probe_gemm_bf16(const void* A, const void* W, int M, int N, int K, void* out_bf16, const float* bias,
                                int variant, void* hip_stream);
 
+/*
+ * Measurement hook: one launch of the bf16 self-attention kernel.  qkv: DEVICE bf16
+ * [slots * tokens][3 * heads * head_dim] (q | k | v), out: DEVICE bf16 [slots * tokens][heads * head_dim].
+ */
+drf_status drf_probe_attn_bf16(const void* qkv, void* out, int slots, int tokens, int heads, int head_dim,
+                               void* hip_stream);
+
 /* HOST, thread-local, valid until the next failing call on this thread. */
 const char* drf_last_error(void);
 

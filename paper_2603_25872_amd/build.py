@@ -13,9 +13,14 @@ FLAGS = ["-x", "hip", "--offload-arch=gfx950", "-O3", "-std=c++17", "-fPIC", "-W
          "-Xclang", "-target-feature", "-Xclang", "-packed-fp32-ops"]
 
 
+# Per-file extras.  attn.hip: keep MFMA accumulators in ordinary VGPRs; the online softmax reads
+# every score right after the MFMA, and AGPR accumulators would cost one move per value per tile.
+EXTRA = {"attn.hip": ["-mllvm", "-amdgpu-mfma-vgpr-form=1"]}
+
+
 def _compile(src):
     out = os.path.join(OBJ, src + ".o")
-    subprocess.check_call(["hipcc", *FLAGS, "-c", os.path.join(CSRC, src), "-o", out])
+    subprocess.check_call(["hipcc", *FLAGS, *EXTRA.get(src, []), "-c", os.path.join(CSRC, src), "-o", out])
     return out
 
 

@@ -602,3 +602,14 @@ extern "C" drf_status drf_probe_gemm_bf16(const void* A, const void* W, int M, i
     drf::g_gemm_variant = 0;
     return rc;
 }
+
+extern "C" drf_status drf_probe_attn_bf16(const void* qkv, void* out, int slots, int tokens, int heads, int head_dim,
+                                          void* hip_stream)
+{
+    if (!qkv || !out || slots < 0 || tokens < 1 || heads < 1 || head_dim < 1) DRF_FAIL(DRF_EINVAL, "bad argument");
+    const int D = heads * head_dim;
+    AttnArgs aa{};
+    aa.q = qkv; aa.ldq = 3 * D; aa.k = (const bf16_t*)qkv + D; aa.v = (const bf16_t*)qkv + 2 * D; aa.ldk = 3 * D;
+    aa.out = out; aa.ldo = D; aa.Nq = tokens; aa.Nk = tokens; aa.heads = heads; aa.d = head_dim; aa.slots = slots; aa.kv_mod = 0;
+    return launch_attn_bf16(aa, (hipStream_t)hip_stream);
+}

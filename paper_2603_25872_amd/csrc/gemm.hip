@@ -521,6 +521,9 @@ drf_status launch_gemm_bf16(const bf16_t* A, const bf16_t* W, int M, int N, int 
     case 6: return launch_bf16_xl<256, 288, 64, 2, 4, 3>(A, W, M, N, K, e, st);
     case 7: return launch_bf16_xl<128, 144, 64, 2, 4, 1>(A, W, M, N, K, e, st);
     case 30: return launch_bf16_xl<256, 288, 32, 4, 4, 2, true>(A, W, M, N, K, e, st);
+    case 34: return launch_bf16_xl<128, 288, 32, 2, 2, 2>(A, W, M, N, K, e, st);
+    case 35: return launch_bf16_xl<128, 288, 32, 3, 2, 2, true>(A, W, M, N, K, e, st);
+    case 36: return launch_bf16_xl<128, 288, 32, 3, 2, 2>(A, W, M, N, K, e, st);
     case 31: return launch_bf16_xl<256, 288, 32, 3, 4, 2, true>(A, W, M, N, K, e, st);
     case 32: return launch_bf16_xl<256, 288, 32, 4, 4, 3, true>(A, W, M, N, K, e, st);
     case 33: return launch_bf16_xl<256, 256, 32, 4, 4, 2, true>(A, W, M, N, K, e, st);

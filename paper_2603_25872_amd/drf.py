@@ -19,7 +19,7 @@ PROF_GEMM, PROF_ATTN, PROF_ELEMWISE, PROF_UPDATE = 0, 1, 2, 3
 
 SYMBOLS = ["drf_denoiser_weight_count", "drf_denoiser_create", "drf_denoiser_destroy", "drf_denoiser_reserve",
            "drf_eps_batched", "drf_eps_trace", "drf_skip_transition", "drf_refine_step", "drf_sample",
-           "drf_plan_build", "drf_profile_enable", "drf_profile_read", "drf_probe_gemm_bf16", "drf_last_error"]
+           "drf_plan_build", "drf_profile_enable", "drf_profile_read", "drf_probe_gemm_bf16", "drf_probe_attn_bf16", "drf_last_error"]
 
 
 class DitConfig(C.Structure):
@@ -68,6 +68,7 @@ def lib():
         L.drf_profile_read.argtypes = [C.c_void_p, C.c_int, C.c_void_p, C.c_void_p, C.c_void_p]
         L.drf_probe_gemm_bf16.argtypes = [C.c_void_p, C.c_void_p, C.c_int, C.c_int, C.c_int, C.c_void_p, C.c_void_p,
                                           C.c_int, C.c_void_p]
+        L.drf_probe_attn_bf16.argtypes = [C.c_void_p, C.c_void_p, C.c_int, C.c_int, C.c_int, C.c_int, C.c_void_p]
         L.drf_last_error.restype = C.c_char_p
         _lib = L
     return _lib
@@ -153,6 +154,16 @@ def probe_gemm_bf16(A, W, bias, out=None, variant=0):
         out = torch.empty((M, N), dtype=torch.bfloat16, device=A.device)
     _check(lib().drf_probe_gemm_bf16(_dev(A, torch.bfloat16), _dev(W, torch.bfloat16), M, N, K,
                                      _dev(out, torch.bfloat16), _dev(bias, torch.float32), variant, _stream()))
+    return out
+
+
+def probe_attn_bf16(qkv, slots, tokens, heads, head_dim, out=None):
+    """Self-attention of the library on a packed bf16 [slots*tokens, 3*heads*head_dim] tensor (measurement hook)."""
+    import torch
+    if out is None:
+        out = torch.empty((slots * tokens, heads * head_dim), dtype=torch.bfloat16, device=qkv.device)
+    _check(lib().drf_probe_attn_bf16(_dev(qkv, torch.bfloat16), _dev(out, torch.bfloat16), slots, tokens, heads, head_dim,
+                                     _stream()))
     return out
 
 
