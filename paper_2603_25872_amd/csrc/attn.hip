@@ -37,9 +37,9 @@ __global__ void __launch_bounds__(256) attn_bf16_kernel(const AttnArgs a, float 
     const int tid = threadIdx.x, lane = tid & 63, wave = tid >> 6, l32 = lane & 31, half = lane >> 5;
     const int slot = blockIdx.z, h = blockIdx.y, d = a.d;
     const int kvb = a.kv_mod ? slot % a.kv_mod : slot;
-    const bf16_t* Q = (const bf16_t*)a.q + (size_t)slot * a.Nq * a.ldq + h * d;
-    const bf16_t* Kp = (const bf16_t*)a.k + (size_t)kvb * a.Nk * a.ldk + h * d;
-    const bf16_t* Vp = (const bf16_t*)a.v + (size_t)kvb * a.Nk * a.ldk + h * d;
+    const bf16_t* Q = (const bf16_t*)a.q + slot * a.q_slot_stride + h * a.q_head_stride;
+    const bf16_t* Kp = (const bf16_t*)a.k + kvb * a.kv_batch_stride + h * a.kv_head_stride;
+    const bf16_t* Vp = (const bf16_t*)a.v + kvb * a.kv_batch_stride + h * a.kv_head_stride;
 
     // zero the padding that loads never touch: K columns [d, DK), V^T rows [d, DT*32)
     for (int i = tid; i < kKvb * LDKS; i += 256) sK[i] = (bf16_t)0.f;
@@ -208,9 +208,9 @@ __global__ void __launch_bounds__(128) attn_f32_kernel(const AttnArgs a, float s
     const int q = blockIdx.x * blockDim.x + threadIdx.x;
     if (q >= a.Nq) return;
     const int kvb = a.kv_mod ? slot % a.kv_mod : slot;
-    const float* Q = (const float*)a.q + ((size_t)slot * a.Nq + q) * a.ldq + h * d;
-    const float* Kp = (const float*)a.k + (size_t)kvb * a.Nk * a.ldk + h * d;
-    const float* Vp = (const float*)a.v + (size_t)kvb * a.Nk * a.ldk + h * d;
+    const float* Q = (const float*)a.q + slot * a.q_slot_stride + h * a.q_head_stride + (size_t)q * a.ldq;
+    const float* Kp = (const float*)a.k + kvb * a.kv_batch_stride + h * a.kv_head_stride;
+    const float* Vp = (const float*)a.v + kvb * a.kv_batch_stride + h * a.kv_head_stride;
     float qv[kF32MaxD], o[kF32MaxD];
     for (int e = 0; e < d; ++e) { qv[e] = Q[e] * scale; o[e] = 0.f; }
     float m_run = -INFINITY, l_run = 0.f;

@@ -72,7 +72,7 @@ struct SlotMap {
     int cond_mod;           // cond row of slot j = cond_mod ? j % cond_mod : j
 };
 
-enum EpiMode { EPI_STORE = 0, EPI_STORE_GELU = 1, EPI_RESID = 2 };
+enum EpiMode { EPI_STORE = 0, EPI_STORE_GELU = 1, EPI_RESID = 2, EPI_STORE_HEADS = 3 };
 struct Epilogue {
     int mode;
     void* out;              // EPI_STORE*: [M][ldo] of out type; EPI_RESID: float [M][ldo], read-modify-write
@@ -82,7 +82,13 @@ struct Epilogue {
     const float* gate;      // EPI_RESID: gate[(m / rows_per_slot) * gate_ld + n], NULL = ungated
     int gate_ld, rows_per_slot;
     uint32_t rps_magic; int rps_shift;   // m / rows_per_slot == fast_div(m, rps_magic, rps_shift), see set_rows_per_slot
+    // EPI_STORE_HEADS (bf16 only): column n = which * hid + head * hd + dd of row m = slot * rows_per_slot + t goes to
+    //   out[which * plane + ((slot * heads + head) * rows_per_slot + t) * hd + dd]     (q | k | v planes, head-major)
+    int hid, hd, heads; size_t plane;
+    uint32_t hid_magic, hd_magic; int hid_shift, hd_shift;
 };
+// Division constants for floor(n / d), 0 <= n < 2^31 (see fast_div in gemm.hip).
+void make_fast_div(int d, uint32_t* magic, int* shift);
 // Fills rows_per_slot and its division constants (exact for 0 <= m < 2^31).
 void set_rows_per_slot(Epilogue* e, int rows_per_slot);
 // C[M][N] = A[M][K] . W[N][K]^T, then the epilogue.  bf16: K % 64 == 0.
@@ -90,9 +96,13 @@ drf_status launch_gemm_bf16(const bf16_t* A, const bf16_t* W, int M, int N, int 
 drf_status launch_gemm_f32(const float* A, const float* W, int M, int N, int K, const Epilogue& e, hipStream_t st);
 
 struct AttnArgs {
-    const void* q; int ldq;         // row (slot * Nq + i), head h at column h * d
-    const void* k; const void* v; int ldk;   // row (kv_batch * Nk + j)
-    void* out; int ldo;
+    // query i of (slot, head h) starts at q + slot * q_slot_stride + h * q_head_stride + i * ldq  (elements);
+    // key/value j at k|v + kv_batch * kv_batch_stride + h * kv_head_stride + j * ldk.
+    // Packed rows [row][.. head h at column h*d ..]: slot stride N * ld, head stride d.
+    // Head-major [slot][head][row][d]: slot stride heads * N * d, head stride N * d, ld = d.
+    const void* q; int ldq; size_t q_slot_stride, q_head_stride;
+    const void* k; const void* v; int ldk; size_t kv_batch_stride, kv_head_stride;
+    void* out; int ldo;             // out row (slot * Nq + i), head h at column h * d
     int Nq, Nk, heads, d, slots;
     int kv_mod;                     // kv_batch = kv_mod ? slot % kv_mod : slot
 };

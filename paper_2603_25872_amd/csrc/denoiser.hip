@@ -194,6 +194,17 @@ Epilogue epi_store(void* out, int ldo, bool f32, bool gelu = false)
     return e;
 }
 
+Epilogue epi_heads(void* out, int M, const DitDims& dm)
+{
+    Epilogue e{};
+    e.mode = EPI_STORE_HEADS; e.out = out; e.ldo = 3 * dm.D; e.out_f32 = 0;
+    set_rows_per_slot(&e, dm.T);
+    e.hid = dm.D; e.hd = dm.d; e.heads = dm.heads; e.plane = (size_t)M * dm.D;
+    make_fast_div(dm.D, &e.hid_magic, &e.hid_shift);
+    make_fast_div(dm.d, &e.hd_magic, &e.hd_shift);
+    return e;
+}
+
 Epilogue epi_resid(float* resid, int ldo, const float* gate, int gate_ld, int rows_per_slot)
 {
     Epilogue e{};
@@ -257,12 +268,22 @@ drf_status forward(drf_denoiser* d, const float* x, const SlotMap& map, const vo
             ProfScope ps(d, st, DRF_PROF_ELEMWISE, ln_bytes);
             if ((rc = launch_ln_modulate(d->resid, mrow, mrow + D, nm, dm.T, M, D, d->hbuf, f32, st)) != DRF_OK) return rc;
         }
-        if ((rc = gemm(d, d->hbuf, b.qkv, M, epi_store(d->qkv, 3 * D, f32), st)) != DRF_OK) return rc;
+        // bf16: q | k | v are stored head-major ([slot][head][token][d] planes) so that attention reads
+        // whole contiguous tiles; fp32: packed rows
+        if ((rc = gemm(d, d->hbuf, b.qkv, M, f32 ? epi_store(d->qkv, 3 * D, true) : epi_heads(d->qkv, M, dm), st)) != DRF_OK) return rc;
         {
             AttnArgs aa{};
-            aa.q = d->qkv; aa.ldq = 3 * D; aa.k = (char*)d->qkv + (size_t)D * act; aa.v = (char*)d->qkv + (size_t)2 * D * act;
-            aa.ldk = 3 * D; aa.out = d->hbuf; aa.ldo = D; aa.Nq = dm.T; aa.Nk = dm.T; aa.heads = dm.heads; aa.d = dm.d;
+            aa.q = d->qkv; aa.out = d->hbuf; aa.ldo = D; aa.Nq = dm.T; aa.Nk = dm.T; aa.heads = dm.heads; aa.d = dm.d;
             aa.slots = slots; aa.kv_mod = 0;
+            if (f32) {
+                aa.k = (char*)d->qkv + (size_t)D * act; aa.v = (char*)d->qkv + (size_t)2 * D * act;
+                aa.ldq = aa.ldk = 3 * D;
+                aa.q_slot_stride = aa.kv_batch_stride = (size_t)dm.T * 3 * D; aa.q_head_stride = aa.kv_head_stride = dm.d;
+            } else {
+                aa.k = (char*)d->qkv + (size_t)M * D * act; aa.v = (char*)d->qkv + (size_t)2 * M * D * act;
+                aa.ldq = aa.ldk = dm.d;
+                aa.q_slot_stride = aa.kv_batch_stride = (size_t)dm.T * D; aa.q_head_stride = aa.kv_head_stride = (size_t)dm.T * dm.d;
+            }
             ProfScope ps(d, st, DRF_PROF_ATTN, 4.0 * slots * dm.heads * (double)dm.T * dm.T * dm.d);
             if ((rc = f32 ? launch_attn_f32(aa, st) : launch_attn_bf16(aa, st)) != DRF_OK) return rc;
         }
@@ -277,6 +298,8 @@ drf_status forward(drf_denoiser* d, const float* x, const SlotMap& map, const vo
             const char* kv = (const char*)d->xkv + (size_t)l * ctx_rows * d->cfg.ctx_len * 2 * D * act;
             AttnArgs aa{};
             aa.q = d->qkv; aa.ldq = D; aa.k = kv; aa.v = kv + (size_t)D * act; aa.ldk = 2 * D; aa.out = d->hbuf; aa.ldo = D;
+            aa.q_slot_stride = (size_t)dm.T * D; aa.q_head_stride = dm.d;
+            aa.kv_batch_stride = (size_t)d->cfg.ctx_len * 2 * D; aa.kv_head_stride = dm.d;
             aa.Nq = dm.T; aa.Nk = d->cfg.ctx_len; aa.heads = dm.heads; aa.d = dm.d; aa.slots = slots; aa.kv_mod = map.cond_mod;
             {
                 ProfScope ps(d, st, DRF_PROF_ATTN, 4.0 * slots * dm.heads * (double)dm.T * d->cfg.ctx_len * dm.d);
@@ -610,6 +633,7 @@ extern "C" drf_status drf_probe_attn_bf16(const void* qkv, void* out, int slots,
     const int D = heads * head_dim;
     AttnArgs aa{};
     aa.q = qkv; aa.ldq = 3 * D; aa.k = (const bf16_t*)qkv + D; aa.v = (const bf16_t*)qkv + 2 * D; aa.ldk = 3 * D;
+    aa.q_slot_stride = aa.kv_batch_stride = (size_t)tokens * 3 * D; aa.q_head_stride = aa.kv_head_stride = head_dim;
     aa.out = out; aa.ldo = D; aa.Nq = tokens; aa.Nk = tokens; aa.heads = heads; aa.d = head_dim; aa.slots = slots; aa.kv_mod = 0;
     return launch_attn_bf16(aa, (hipStream_t)hip_stream);
 }

@@ -28,6 +28,16 @@ __device__ inline int fast_div(int n, uint32_t magic, int shift)
     return magic ? (int)(__umulhi((uint32_t)n, magic) >> shift) : (n >> shift);
 }
 
+// Element offset of (row m, column n) in the head-major q | k | v planes (n is a multiple of 4 or 8
+// and the head width a multiple of 8, so a vector never straddles a head).
+__device__ inline size_t heads_offset(const Epilogue& e, int m, int n)
+{
+    const int which = fast_div(n, e.hid_magic, e.hid_shift), c = n - which * e.hid;
+    const int head = fast_div(c, e.hd_magic, e.hd_shift), dd = c - head * e.hd;
+    const int slot = fast_div(m, e.rps_magic, e.rps_shift), t = m - slot * e.rows_per_slot;
+    return (size_t)which * e.plane + ((size_t)(slot * e.heads + head) * e.rows_per_slot + t) * e.hd + dd;
+}
+
 // Applies the epilogue to 4 consecutive columns n..n+3 of row m (n % 4 == 0, n + 3 < N).
 __device__ inline void epilogue4(const Epilogue& e, int m, int n, float v0, float v1, float v2, float v3)
 {
@@ -50,7 +60,8 @@ __device__ inline void epilogue4(const Epilogue& e, int m, int n, float v0, floa
         *reinterpret_cast<float4*>((float*)e.out + (size_t)m * e.ldo + n) = make_float4(v0, v1, v2, v3);
     } else {
         bf16x4 o = { (bf16_t)v0, (bf16_t)v1, (bf16_t)v2, (bf16_t)v3 };
-        *reinterpret_cast<bf16x4*>((bf16_t*)e.out + (size_t)m * e.ldo + n) = o;
+        const size_t off = e.mode == EPI_STORE_HEADS ? heads_offset(e, m, n) : (size_t)m * e.ldo + n;
+        *reinterpret_cast<bf16x4*>((bf16_t*)e.out + off) = o;
     }
 }
 
@@ -404,9 +415,10 @@ gemm_bf16_xl_kernel(const bf16_t* __restrict__ A, const bf16_t* __restrict__ W, 
             for (int id = lane; id < RPP * CH; id += 64) {
                 const int rl = id / CH, c = id % CH;
                 const int m = mw + j0 * 16 + rl, n = nw + c * 8;
-                if (j0 * 16 + rl < TM && m < M && n < N)
-                    *reinterpret_cast<bf16x8*>((bf16_t*)e.out + (size_t)m * e.ldo + n) =
-                        *reinterpret_cast<const bf16x8*>(wbuf + rl * ROWB + c * 16);
+                if (j0 * 16 + rl < TM && m < M && n < N) {
+                    const size_t off = e.mode == EPI_STORE_HEADS ? heads_offset(e, m, n) : (size_t)m * e.ldo + n;
+                    *reinterpret_cast<bf16x8*>((bf16_t*)e.out + off) = *reinterpret_cast<const bf16x8*>(wbuf + rl * ROWB + c * 16);
+                }
             }
         }
     }
@@ -491,6 +503,8 @@ drf_status launch_gemm_bf16(const bf16_t* A, const bf16_t* W, int M, int N, int 
 {
     if (M == 0 || N == 0) return DRF_OK;
     if (K % 64 != 0 || N % 4 != 0 || e.ldo % 4 != 0) DRF_FAIL(DRF_ESHAPE, "bf16 GEMM needs K %% 64 == 0 and N %% 4 == 0 (M=%d N=%d K=%d)", M, N, K);
+    if (e.mode == EPI_STORE_HEADS && (e.out_f32 || e.hd % 8 != 0 || N % e.hid != 0))
+        DRF_FAIL(DRF_ESHAPE, "head-major store needs bf16 output and head width %% 8 == 0");
     if ((size_t)M * K >= ((size_t)1 << 31) || (size_t)N * K >= ((size_t)1 << 31))
         DRF_FAIL(DRF_ESHAPE, "bf16 GEMM operand exceeds 2^31 elements");
     int v = g_gemm_variant;

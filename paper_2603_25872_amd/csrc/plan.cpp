@@ -53,14 +53,19 @@ void Schedule::coef(int s_from, int s_to, float* A, float* B) const
 // Division by an invariant (round-up method): for d not a power of two let s = ceil(log2 d)
 // and magic = floor(2^(31+s) / d) + 1 < 2^32.  Then magic * d - 2^(31+s) <= d <= 2^s, which
 // makes floor(n / d) = (n * magic) >> (31 + s) exact for every 0 <= n < 2^31.
+void make_fast_div(int d, uint32_t* magic, int* shift)
+{
+    int s = 0;
+    while ((1ll << s) < d) ++s;
+    if ((1ll << s) == d) { *magic = 0; *shift = s; return; }
+    *magic = (uint32_t)(((1ull << (31 + s)) / (unsigned long long)d) + 1ull);
+    *shift = s - 1;             // after the high half of the 32 x 32 product
+}
+
 void set_rows_per_slot(Epilogue* e, int d)
 {
     e->rows_per_slot = d;
-    int s = 0;
-    while ((1ll << s) < d) ++s;
-    if ((1ll << s) == d) { e->rps_magic = 0; e->rps_shift = s; return; }
-    e->rps_magic = (uint32_t)(((1ull << (31 + s)) / (unsigned long long)d) + 1ull);
-    e->rps_shift = s - 1;       // after the high half of the 32 x 32 product
+    make_fast_div(d, &e->rps_magic, &e->rps_shift);
 }
 
 namespace {
