@@ -395,6 +395,17 @@ static void attention(real* out, const real* q, size_t ldq, const real* k, const
     }
 }
 
+/* The two building blocks above, exported for kernel-level parity tests. */
+void orc_linear(real* y, const real* x, const real* W, const real* b, size_t M, size_t K, size_t N)
+{
+    linear(y, x, W, b, M, K, N);
+}
+void orc_attention(real* out, const real* q, size_t ldq, const real* k, const real* v, size_t ldk, size_t Nq,
+                   size_t Nk, int heads, size_t d)
+{
+    attention(out, q, ldq, k, v, ldk, Nq, Nk, heads, d);
+}
+
 /* eps_theta(x, tau, cond) for `slots` independent samples, each with its own
  * timestep.  x, eps_out: [slots][in_ch][lat_h][lat_w].
  * cond: vector real [slots][cond_dim] | class int32 [slots] (cond_dim = null class)

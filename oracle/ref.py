@@ -47,6 +47,33 @@ class Oracle:
         L.orc_eps_guided.argtypes = [C.c_void_p, C.c_void_p, C.c_void_p, C.c_int, C.c_void_p,
                                      C.c_void_p, C.c_double, C.c_int, C.c_void_p]
 
+    def linear(self, x, W, b):
+        """y = x W^T + b with the oracle's plain triple loop."""
+        x = np.ascontiguousarray(x, self.real); W = np.ascontiguousarray(W, self.real)
+        b = np.ascontiguousarray(b, self.real)
+        M, K = x.shape
+        N = W.shape[0]
+        y = np.empty((M, N), self.real)
+        self.lib.orc_linear.argtypes = [C.c_void_p] * 4 + [C.c_size_t] * 3
+        self.lib.orc_linear(_ptr(y), _ptr(x), _ptr(W), _ptr(b), M, K, N)
+        return y
+
+    def attention_packed(self, qkv, tokens, heads, d):
+        """Self-attention per slot on packed rows [slots*tokens, 3*heads*d] (q | k | v)."""
+        qkv = np.ascontiguousarray(qkv, self.real)
+        D = heads * d
+        slots = qkv.shape[0] // tokens
+        out = np.empty((slots * tokens, D), self.real)
+        self.lib.orc_attention.argtypes = [C.c_void_p, C.c_void_p, C.c_size_t, C.c_void_p, C.c_void_p, C.c_size_t,
+                                           C.c_size_t, C.c_size_t, C.c_int, C.c_size_t]
+        item = qkv.itemsize
+        for s in range(slots):
+            base = qkv.ctypes.data + s * tokens * 3 * D * item
+            self.lib.orc_attention(C.c_void_p(out.ctypes.data + s * tokens * D * item), C.c_void_p(base), 3 * D,
+                                   C.c_void_p(base + D * item), C.c_void_p(base + 2 * D * item), 3 * D, tokens, tokens,
+                                   heads, d)
+        return out
+
     def threads(self):
         return int(self.lib.orc_num_threads())
 

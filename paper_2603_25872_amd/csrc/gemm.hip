@@ -1,8 +1,6 @@
 // GEMM C[M][N] = A[M][K] . W[N][K]^T with fused epilogues (bias, GELU-tanh, gated
 // residual).  bf16 path: MFMA 32x32x16 tiles fed from LDS, fp32 accumulate.
 // fp32 path: plain LDS-tiled FMA kernel for the fp32 configuration.
-#include <type_traits>
-
 #include "common.h"
 
 namespace drf {
@@ -186,10 +184,10 @@ template <int N> __device__ inline void wait_vmcnt() { asm volatile("s_waitcnt v
 //    consecutive lanes on consecutive addresses.
 typedef float f32x4 __attribute__((ext_vector_type(4)));
 
-template <int BM, int BN, int BK, int NS, int WM, int WN, bool SP = false>
+template <int BM, int BN, int BK, int NS, int WM, int WN>
 __global__ void __launch_bounds__(WM * WN * 64)
 gemm_bf16_xl_kernel(const bf16_t* __restrict__ A, const bf16_t* __restrict__ W, int M, int N, int K, const Epilogue e,
-                    int tiles_m, int tiles_n, int dbg)
+                    int tiles_m, int tiles_n)
 {
     constexpr int NW = WM * WN, TM = BM / WM, TN = BN / WN, MI = TM / 16, NI = TN / 16, KS = BK / 32;
     constexpr int CPR = BK / 8, RPI = 64 / CPR, RB = 256 / (BK * 2);
@@ -231,7 +229,6 @@ gemm_bf16_xl_kernel(const bf16_t* __restrict__ A, const bf16_t* __restrict__ W, 
         voff[i] = ((uint32_t)row * (uint32_t)K + (uint32_t)chunk * 8u) * 2u;
     }
     auto issue = [&](int kt, int stage) {
-        if ((dbg & 1) && kt >= NS) return;                          // timing experiment: no steady-state loads
 #pragma unroll
         for (int i = 0; i < LPT; ++i) {
             int g = wave * LPT + i; g = g < SEG ? g : SEG - 1;
@@ -252,63 +249,6 @@ gemm_bf16_xl_kernel(const bf16_t* __restrict__ A, const bf16_t* __restrict__ W, 
     for (int ks = 0; ks < KS; ++ks) koff[ks] = l16 * BK + (((ks * 4 + quarter) ^ ((l16 / RB) & (CPR - 1))) << 3);
 
     const int nk = K / BK;
-    if constexpr (SP) {
-        // Software-pipelined loop (BK = 32, one 16x16x32 k-step per stage).  While the MFMAs of
-        // k-tile t are issued, the operands of k-tile t+1 are fetched from LDS: each weight
-        // fragment is reloaded right after its last MFMA (same registers), the activation
-        // fragments are double-buffered.  Tile t+1 is known to have landed at the barrier of
-        // iteration t, and the stage of tile t (already in registers) is refilled right away,
-        // so NS-1 tiles are in flight.
-        static_assert(BK == 32 && KS == 1 && NS >= 3, "software-pipelined loop needs BK = 32 and >= 3 stages");
-        bf16x8 fa[2][MI], fw[NI];
-#pragma unroll
-        for (int s = 0; s < NS - 1; ++s)
-            if (s < nk) issue(s, s);
-        if (nk >= NS - 1) wait_vmcnt<LPT * (NS - 2)>(); else wait_vmcnt<0>();   // tile 0 has landed
-        __syncthreads();
-        {
-            const bf16_t* pa = smem + wm * TM * BK + koff[0];
-            const bf16_t* pw = smem + BM * BK + wn * TN * BK + koff[0];
-#pragma unroll
-            for (int j = 0; j < MI; ++j) fa[0][j] = *reinterpret_cast<const bf16x8*>(pa + j * 16 * BK);
-#pragma unroll
-            for (int i = 0; i < NI; ++i) fw[i] = *reinterpret_cast<const bf16x8*>(pw + i * 16 * BK);
-        }
-        auto body = [&](int kt, auto cur_c) {
-            constexpr int cur = decltype(cur_c)::value, nxt = cur ^ 1;
-            const bf16_t* pa = smem + ((kt + 1) % NS) * STAGE + wm * TM * BK + koff[0];
-            const bf16_t* pw = smem + ((kt + 1) % NS) * STAGE + BM * BK + wn * TN * BK + koff[0];
-            if (kt + 1 < nk) {
-                // tile kt+1 has landed once only the NS-3 younger tiles remain in flight
-                if (kt + NS - 2 < nk) wait_vmcnt<LPT * (NS - 3)>(); else wait_vmcnt<0>();
-                // A bare s_barrier: __syncthreads() would also drain every LDS-DMA in flight.  After
-                // it tile kt+1 is visible to all waves, and all of them have consumed (hence finished
-                // reading) tile kt-1, whose stage is refilled next.
-                asm volatile("" ::: "memory");
-                __builtin_amdgcn_s_barrier();
-                asm volatile("" ::: "memory");
-                if (kt + NS - 1 < nk) issue(kt + NS - 1, (kt + NS - 1) % NS);
-            }
-            // (after the last tile the fetches below read a stale stage; the values are never used)
-            __builtin_amdgcn_sched_barrier(0);
-#pragma unroll
-            for (int i = 0; i < NI; ++i) {
-                __builtin_amdgcn_s_setprio(1);
-#pragma unroll
-                for (int j = 0; j < MI; ++j)
-                    acc[i][j] = __builtin_amdgcn_mfma_f32_16x16x32_bf16(fw[i], fa[cur][j], acc[i][j], 0, 0, 0);
-                __builtin_amdgcn_s_setprio(0);
-                fw[i] = *reinterpret_cast<const bf16x8*>(pw + i * 16 * BK);
-                if (i < MI) fa[nxt][i] = *reinterpret_cast<const bf16x8*>(pa + i * 16 * BK);
-                __builtin_amdgcn_sched_barrier(0);
-            }
-            static_assert(MI <= NI, "activation fragments are fetched one per weight fragment");
-        };
-        for (int kt = 0; kt < nk; kt += 2) {
-            body(kt, std::integral_constant<int, 0>{});
-            if (kt + 1 < nk) body(kt + 1, std::integral_constant<int, 1>{});
-        }
-    } else {
 #pragma unroll
     for (int s = 0; s < NS - 1; ++s)
         if (s < nk) issue(s, s);
@@ -336,8 +276,6 @@ gemm_bf16_xl_kernel(const bf16_t* __restrict__ A, const bf16_t* __restrict__ W, 
             __builtin_amdgcn_s_setprio(0);
         }
     }
-    }
-    if ((dbg & 4) && acc[0][0][0] != 12345.678f) return;            // timing experiment: no epilogue
 
     // ---- epilogue through LDS: acc[i][j][r] is (m = j*16 + l16, n = i*16 + 4*quarter + r) of the wave tile
     __syncthreads();
@@ -417,7 +355,10 @@ gemm_bf16_xl_kernel(const bf16_t* __restrict__ A, const bf16_t* __restrict__ W, 
                 const int m = mw + j0 * 16 + rl, n = nw + c * 8;
                 if (j0 * 16 + rl < TM && m < M && n < N) {
                     const size_t off = e.mode == EPI_STORE_HEADS ? heads_offset(e, m, n) : (size_t)m * e.ldo + n;
-                    *reinterpret_cast<bf16x8*>((bf16_t*)e.out + off) = *reinterpret_cast<const bf16x8*>(wbuf + rl * ROWB + c * 16);
+                    if (n + 8 <= N)
+                        *reinterpret_cast<bf16x8*>((bf16_t*)e.out + off) = *reinterpret_cast<const bf16x8*>(wbuf + rl * ROWB + c * 16);
+                    else                    // N is a multiple of 4: the last chunk of a row may be half valid
+                        *reinterpret_cast<bf16x4*>((bf16_t*)e.out + off) = *reinterpret_cast<const bf16x4*>(wbuf + rl * ROWB + c * 16);
                 }
             }
         }
@@ -476,21 +417,18 @@ drf_status launch_bf16_tile(const bf16_t* A, const bf16_t* W, int M, int N, int 
     return DRF_OK;
 }
 
-int g_gemm_debug = 0;   // timing experiments only (results are wrong when non-zero)
-
-template <int BM, int BN, int BK, int NS, int WM, int WN, bool SP = false>
+template <int BM, int BN, int BK, int NS, int WM, int WN>
 drf_status launch_bf16_xl(const bf16_t* A, const bf16_t* W, int M, int N, int K, const Epilogue& e, hipStream_t st)
 {
     constexpr size_t smem = (size_t)NS * (BM + BN) * BK * sizeof(bf16_t);
     static bool attr_set = false;
-    auto kern = gemm_bf16_xl_kernel<BM, BN, BK, NS, WM, WN, SP>;
+    auto kern = gemm_bf16_xl_kernel<BM, BN, BK, NS, WM, WN>;
     if (!attr_set) {
         DRF_HIP(hipFuncSetAttribute(reinterpret_cast<const void*>(kern), hipFuncAttributeMaxDynamicSharedMemorySize, (int)smem));
         attr_set = true;
     }
     const int tiles_m = (M + BM - 1) / BM, tiles_n = (N + BN - 1) / BN;
-    hipLaunchKernelGGL(kern, dim3(tiles_m * tiles_n), dim3(WM * WN * 64), smem, st, A, W, M, N, K, e, tiles_m, tiles_n,
-                       g_gemm_debug);
+    hipLaunchKernelGGL(kern, dim3(tiles_m * tiles_n), dim3(WM * WN * 64), smem, st, A, W, M, N, K, e, tiles_m, tiles_n);
     DRF_HIP(hipGetLastError());
     return DRF_OK;
 }
@@ -508,8 +446,6 @@ drf_status launch_gemm_bf16(const bf16_t* A, const bf16_t* W, int M, int N, int 
     if ((size_t)M * K >= ((size_t)1 << 31) || (size_t)N * K >= ((size_t)1 << 31))
         DRF_FAIL(DRF_ESHAPE, "bf16 GEMM operand exceeds 2^31 elements");
     int v = g_gemm_variant;
-    g_gemm_debug = v / 100;
-    v %= 100;
     if (v == 0) {
         // Pick the tile shape that wastes the least MFMA work: padding of the last tile row /
         // column, and the idle CUs of the last round of 256 concurrent tiles.
@@ -534,13 +470,6 @@ drf_status launch_gemm_bf16(const bf16_t* A, const bf16_t* W, int M, int N, int 
     case 5: return launch_bf16_xl<128, 128, 64, 2, 2, 2>(A, W, M, N, K, e, st);
     case 6: return launch_bf16_xl<256, 288, 64, 2, 4, 3>(A, W, M, N, K, e, st);
     case 7: return launch_bf16_xl<128, 144, 64, 2, 4, 1>(A, W, M, N, K, e, st);
-    case 30: return launch_bf16_xl<256, 288, 32, 4, 4, 2, true>(A, W, M, N, K, e, st);
-    case 34: return launch_bf16_xl<128, 288, 32, 2, 2, 2>(A, W, M, N, K, e, st);
-    case 35: return launch_bf16_xl<128, 288, 32, 3, 2, 2, true>(A, W, M, N, K, e, st);
-    case 36: return launch_bf16_xl<128, 288, 32, 3, 2, 2>(A, W, M, N, K, e, st);
-    case 31: return launch_bf16_xl<256, 288, 32, 3, 4, 2, true>(A, W, M, N, K, e, st);
-    case 32: return launch_bf16_xl<256, 288, 32, 4, 4, 3, true>(A, W, M, N, K, e, st);
-    case 33: return launch_bf16_xl<256, 256, 32, 4, 4, 2, true>(A, W, M, N, K, e, st);
     default: return launch_bf16_tile<128, 128, 2, 2>(A, W, M, N, K, e, st);
     }
 }
