@@ -184,15 +184,18 @@ template <int N> __device__ inline void wait_vmcnt() { asm volatile("s_waitcnt v
 //    consecutive lanes on consecutive addresses.
 typedef float f32x4 __attribute__((ext_vector_type(4)));
 
-template <int BM, int BN, int BK, int NS, int WM, int WN>
-__global__ void __launch_bounds__(WM * WN * 64)
+template <int BM, int BN, int BK, int NS, int WM, int WN, int WK = 1>
+__global__ void __launch_bounds__(WM * WN * WK * 64)
 gemm_bf16_xl_kernel(const bf16_t* __restrict__ A, const bf16_t* __restrict__ W, int M, int N, int K, const Epilogue e,
                     int tiles_m, int tiles_n)
 {
-    constexpr int NW = WM * WN, TM = BM / WM, TN = BN / WN, MI = TM / 16, NI = TN / 16, KS = BK / 32;
+    // WK > 1: the waves form WK groups that share the output tile and split K between them (group g
+    // takes the k-tiles g, g + WK, ...); the groups' partial sums are added through LDS before the
+    // epilogue.  This doubles the waves per CU for shapes that only yield one small tile per CU.
+    constexpr int NWT = WM * WN, NW = NWT * WK, TM = BM / WM, TN = BN / WN, MI = TM / 16, NI = TN / 16, KS = BK / 32;
     constexpr int CPR = BK / 8, RPI = 64 / CPR, RB = 256 / (BK * 2);
-    constexpr int SEG = (BM + BN) / RPI, LPT = (SEG + NW - 1) / NW;
-    constexpr int STAGE = (BM + BN) * BK;
+    constexpr int STAGE1 = (BM + BN) * BK, STAGE = WK * STAGE1;
+    constexpr int SEG1 = (BM + BN) / RPI, SEG = WK * SEG1, LPT = (SEG + NW - 1) / NW;
     constexpr int GROUP_M = 8;
     static_assert(TM % 16 == 0 && TN % 16 == 0 && (BM + BN) % RPI == 0 && BM % 16 == 0, "tile shape");
     extern __shared__ __attribute__((aligned(16))) unsigned char smem_raw[];
@@ -208,23 +211,23 @@ gemm_bf16_xl_kernel(const bf16_t* __restrict__ A, const bf16_t* __restrict__ W, 
 
     const int tid = threadIdx.x, lane = tid & 63;
     const int wave = __builtin_amdgcn_readfirstlane(tid >> 6);      // wave-uniform, kept in a scalar register
-    const int wm = wave % WM, wn = wave / WM;
+    const int wk = wave / NWT, wl = wave % NWT, wm = wl % WM, wn = wl / WM;
     const int l16 = lane & 15, quarter = lane >> 4;
 
-    // DMA: the A rows and W rows of a stage form one row space [0, BM + BN); a wave-wide
-    // instruction covers RPI rows of it (never straddling the A/W boundary).  Every wave issues
-    // LPT instructions; when SEG is not a multiple of the wave count the surplus ones repeat the
-    // last segment (same bytes, same place).  Per lane only a 32-bit byte offset is kept; the
-    // matrix base and the LDS destination are wave-uniform.
+    // DMA: the A rows and W rows of a k-tile form one row space [0, BM + BN), and a stage holds WK
+    // k-tiles one after the other.  A wave-wide instruction covers RPI rows (never straddling the
+    // A/W boundary).  Every wave issues LPT instructions; when SEG is not a multiple of the wave
+    // count the surplus ones repeat the last segment (same bytes, same place).  Per lane only a
+    // 32-bit byte offset is kept; the matrix base and the LDS destination are wave-uniform.
     const int prow = lane / CPR, ppos = lane % CPR;
     uint32_t voff[LPT];
 #pragma unroll
     for (int i = 0; i < LPT; ++i) {
         int g = wave * LPT + i; g = g < SEG ? g : SEG - 1;
-        const int r = g * RPI + prow;
+        const int gl = g % SEG1, r = gl * RPI + prow;
         const int chunk = ppos ^ ((r / RB) & (CPR - 1));
         int row;
-        if (g * RPI < BM) { row = m0 + r; row = row < M ? row : M - 1; }
+        if (gl * RPI < BM) { row = m0 + r; row = row < M ? row : M - 1; }
         else { row = n0 + r - BM; row = row < N ? row : N - 1; }
         voff[i] = ((uint32_t)row * (uint32_t)K + (uint32_t)chunk * 8u) * 2u;
     }
@@ -232,9 +235,10 @@ gemm_bf16_xl_kernel(const bf16_t* __restrict__ A, const bf16_t* __restrict__ W, 
 #pragma unroll
         for (int i = 0; i < LPT; ++i) {
             int g = wave * LPT + i; g = g < SEG ? g : SEG - 1;
-            const char* base = reinterpret_cast<const char*>((g * RPI < BM ? A : W) + kt * BK);
+            const int sub = g / SEG1, gl = g % SEG1;
+            const char* base = reinterpret_cast<const char*>((gl * RPI < BM ? A : W) + (kt * WK + sub) * BK);
             __builtin_amdgcn_global_load_lds((const DRF_GLOBAL_AS void*)(base + voff[i]),
-                                             (DRF_LDS_AS void*)(smem + stage * STAGE + g * RPI * BK), 16, 0, 0);
+                                             (DRF_LDS_AS void*)(smem + stage * STAGE + sub * STAGE1 + gl * RPI * BK), 16, 0, 0);
         }
     };
 
@@ -248,7 +252,7 @@ gemm_bf16_xl_kernel(const bf16_t* __restrict__ A, const bf16_t* __restrict__ W, 
 #pragma unroll
     for (int ks = 0; ks < KS; ++ks) koff[ks] = l16 * BK + (((ks * 4 + quarter) ^ ((l16 / RB) & (CPR - 1))) << 3);
 
-    const int nk = K / BK;
+    const int nk = K / (BK * WK);
 #pragma unroll
     for (int s = 0; s < NS - 1; ++s)
         if (s < nk) issue(s, s);
@@ -258,8 +262,8 @@ gemm_bf16_xl_kernel(const bf16_t* __restrict__ A, const bf16_t* __restrict__ W, 
         if (kt + NS - 2 < nk) wait_vmcnt<LPT * (NS - 2)>(); else wait_vmcnt<0>();
         __syncthreads();                     // ... for every wave, and all are done reading tile kt-1's stage
         if (kt + NS - 1 < nk) issue(kt + NS - 1, (kt + NS - 1) % NS);
-        const bf16_t* pa = smem + stage * STAGE + wm * TM * BK;
-        const bf16_t* pw = smem + stage * STAGE + BM * BK + wn * TN * BK;
+        const bf16_t* pa = smem + stage * STAGE + wk * STAGE1 + wm * TM * BK;
+        const bf16_t* pw = smem + stage * STAGE + wk * STAGE1 + BM * BK + wn * TN * BK;
 #pragma unroll
         for (int ks = 0; ks < KS; ++ks) {
             bf16x8 fa[MI], fw[NI];
@@ -279,8 +283,27 @@ gemm_bf16_xl_kernel(const bf16_t* __restrict__ A, const bf16_t* __restrict__ W, 
 
     // ---- epilogue through LDS: acc[i][j][r] is (m = j*16 + l16, n = i*16 + 4*quarter + r) of the wave tile
     __syncthreads();
-    constexpr int WBYTES = NS * STAGE * 2 / NW;                     // this wave's private slice of the stages
-    unsigned char* wbuf = smem_raw + wave * WBYTES;
+    constexpr int PART = (WK - 1) * NWT * TM * TN * 4;              // partial sums of the other K groups
+    if constexpr (WK > 1) {
+        static_assert(PART < NS * STAGE * 2, "LDS too small for the split-K partial sums");
+        f32x4* part = reinterpret_cast<f32x4*>(smem_raw);
+        if (wk > 0) {
+#pragma unroll
+            for (int i = 0; i < NI; ++i)
+#pragma unroll
+                for (int j = 0; j < MI; ++j) part[(((wk - 1) * NWT + wl) * NI * MI + i * MI + j) * 64 + lane] = acc[i][j];
+        }
+        __syncthreads();
+        if (wk > 0) return;                                         // the first group finishes the tile
+#pragma unroll
+        for (int g = 0; g < WK - 1; ++g)
+#pragma unroll
+            for (int i = 0; i < NI; ++i)
+#pragma unroll
+                for (int j = 0; j < MI; ++j) acc[i][j] += part[((g * NWT + wl) * NI * MI + i * MI + j) * 64 + lane];
+    }
+    constexpr int WBYTES = (NS * STAGE * 2 - PART) / NWT / 16 * 16; // this wave's private slice of the stages
+    unsigned char* wbuf = smem_raw + PART + wl * WBYTES;
     const int mw = m0 + wm * TM, nw = n0 + wn * TN;
     const bool resid = e.mode == EPI_RESID;
     if (resid || e.out_f32) {
@@ -417,18 +440,19 @@ drf_status launch_bf16_tile(const bf16_t* A, const bf16_t* W, int M, int N, int 
     return DRF_OK;
 }
 
-template <int BM, int BN, int BK, int NS, int WM, int WN>
+template <int BM, int BN, int BK, int NS, int WM, int WN, int WK = 1>
 drf_status launch_bf16_xl(const bf16_t* A, const bf16_t* W, int M, int N, int K, const Epilogue& e, hipStream_t st)
 {
-    constexpr size_t smem = (size_t)NS * (BM + BN) * BK * sizeof(bf16_t);
+    constexpr size_t smem = (size_t)NS * WK * (BM + BN) * BK * sizeof(bf16_t);
     static bool attr_set = false;
-    auto kern = gemm_bf16_xl_kernel<BM, BN, BK, NS, WM, WN>;
+    auto kern = gemm_bf16_xl_kernel<BM, BN, BK, NS, WM, WN, WK>;
+    if (K % (BK * WK) != 0) DRF_FAIL(DRF_ESHAPE, "bf16 GEMM tile needs K %% %d == 0 (K=%d)", BK * WK, K);
     if (!attr_set) {
         DRF_HIP(hipFuncSetAttribute(reinterpret_cast<const void*>(kern), hipFuncAttributeMaxDynamicSharedMemorySize, (int)smem));
         attr_set = true;
     }
     const int tiles_m = (M + BM - 1) / BM, tiles_n = (N + BN - 1) / BN;
-    hipLaunchKernelGGL(kern, dim3(tiles_m * tiles_n), dim3(WM * WN * 64), smem, st, A, W, M, N, K, e, tiles_m, tiles_n);
+    hipLaunchKernelGGL(kern, dim3(tiles_m * tiles_n), dim3(WM * WN * WK * 64), smem, st, A, W, M, N, K, e, tiles_m, tiles_n);
     DRF_HIP(hipGetLastError());
     return DRF_OK;
 }
@@ -461,6 +485,8 @@ drf_status launch_gemm_bf16(const bf16_t* A, const bf16_t* W, int M, int N, int 
                 const double score = c.eff * ((double)M * N) / (rounds * 256.0 * c.bm * c.bn);
                 if (score > best) { best = score; v = c.id; }
             }
+            // one small tile per CU: let two wave groups split K inside the block
+            if (v == 7 && K % 128 == 0 && K >= 1024) v = 8;
         }
     }
     switch (v) {
@@ -470,6 +496,7 @@ drf_status launch_gemm_bf16(const bf16_t* A, const bf16_t* W, int M, int N, int 
     case 5: return launch_bf16_xl<128, 128, 64, 2, 2, 2>(A, W, M, N, K, e, st);
     case 6: return launch_bf16_xl<256, 288, 64, 2, 4, 3>(A, W, M, N, K, e, st);
     case 7: return launch_bf16_xl<128, 144, 64, 2, 4, 1>(A, W, M, N, K, e, st);
+    case 8: return launch_bf16_xl<128, 144, 64, 2, 4, 1, 2>(A, W, M, N, K, e, st);
     default: return launch_bf16_tile<128, 128, 2, 2>(A, W, M, N, K, e, st);
     }
 }
