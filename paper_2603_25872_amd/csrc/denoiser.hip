@@ -43,7 +43,7 @@ struct drf_denoiser {
     std::vector<BlockW> blk;
     float* pos = nullptr;           // [T][D]
     // workspace
-    int cap_slots = 0;
+    int cap_slots = 0, cap_cond_rows = 0;
     float *resid = nullptr, *mod = nullptr, *cact32 = nullptr, *cscratch = nullptr;
     void *hbuf = nullptr, *qkv = nullptr, *mid = nullptr, *cact = nullptr;
     // cross-attention K/V cache [L][rows][ctx_len][2D] and its staging
@@ -144,24 +144,39 @@ struct ProfScope {
     ~ProfScope() { if (live) (void)hipEventRecord(d->prof.pool[d->prof.recs[rec].e1], st); }
 };
 
+// Activation buffers for `slots` samples per pass.
 drf_status ensure_workspace(drf_denoiser* d, int slots, hipStream_t st)
 {
     if (slots <= d->cap_slots) return DRF_OK;
     DRF_HIP(hipStreamSynchronize(st));
-    void* olds[] = { d->resid, d->mod, d->cact32, d->cscratch, d->hbuf, d->qkv, d->mid, d->cact };
+    void* olds[] = { d->resid, d->hbuf, d->qkv, d->mid };
     for (void* p : olds) dev_free(d, p);
     d->cap_slots = 0;
     const size_t M = (size_t)slots * d->dm.T, D = (size_t)d->dm.D, act = d->bf16 ? 2 : 4;
     drf_status rc;
     if ((rc = dev_alloc(d, (void**)&d->resid, M * D * 4)) != DRF_OK) return rc;
-    if ((rc = dev_alloc(d, (void**)&d->mod, (size_t)slots * d->n_mod * 4)) != DRF_OK) return rc;
-    if ((rc = dev_alloc(d, (void**)&d->cact32, (size_t)slots * D * 4)) != DRF_OK) return rc;
-    if ((rc = dev_alloc(d, (void**)&d->cscratch, (size_t)slots * (kTFreq + 3 * D) * 4)) != DRF_OK) return rc;
-    if ((rc = dev_alloc(d, &d->cact, (size_t)slots * D * act)) != DRF_OK) return rc;
     if ((rc = dev_alloc(d, &d->hbuf, M * D * act)) != DRF_OK) return rc;
     if ((rc = dev_alloc(d, &d->qkv, M * 3 * D * act)) != DRF_OK) return rc;
     if ((rc = dev_alloc(d, &d->mid, M * (size_t)d->dm.R * D * act)) != DRF_OK) return rc;
     d->cap_slots = slots;
+    return DRF_OK;
+}
+
+// Conditioning buffers for `rows` slot rows: front-end scratch, SiLU(c), and the modulation table.
+drf_status ensure_cond(drf_denoiser* d, int rows, hipStream_t st)
+{
+    if (rows <= d->cap_cond_rows) return DRF_OK;
+    DRF_HIP(hipStreamSynchronize(st));
+    void* olds[] = { d->mod, d->cact32, d->cscratch, d->cact };
+    for (void* p : olds) dev_free(d, p);
+    d->cap_cond_rows = 0;
+    const size_t D = (size_t)d->dm.D, act = d->bf16 ? 2 : 4;
+    drf_status rc;
+    if ((rc = dev_alloc(d, (void**)&d->mod, (size_t)rows * d->n_mod * 4)) != DRF_OK) return rc;
+    if ((rc = dev_alloc(d, (void**)&d->cact32, (size_t)rows * D * 4)) != DRF_OK) return rc;
+    if ((rc = dev_alloc(d, (void**)&d->cscratch, (size_t)rows * (kTFreq + 3 * D) * 4)) != DRF_OK) return rc;
+    if ((rc = dev_alloc(d, &d->cact, (size_t)rows * D * act)) != DRF_OK) return rc;
+    d->cap_cond_rows = rows;
     return DRF_OK;
 }
 
@@ -232,8 +247,31 @@ drf_status compute_ctx_kv(drf_denoiser* d, const float* ctx, int rows, hipStream
     return DRF_OK;
 }
 
-// The batched forward.  ctx_rows > 0: the cross-attention K/V cache already holds that many rows.
-drf_status forward(drf_denoiser* d, const float* x, const SlotMap& map, const void* cond, int slots, int n_blocks,
+// Conditioning of `rows` slot rows (they need not belong to one pass): c = MLP(femb(tau)) + cond
+// embedding per row, then every block's shift / scale / gate and the final layer's in ONE GEMM
+// against the stacked adaLN projections.  Row r of the result is mod_out[r][0 .. n_mod).
+drf_status conditioning(drf_denoiser* d, const SlotMap& map, const void* cond, int rows, int row0, float* mod_out,
+                        hipStream_t st)
+{
+    const int D = d->dm.D;
+    drf_status rc;
+    CondArgs ca{};
+    ca.t_w1 = d->t_w1; ca.t_b1 = d->t_b1; ca.t_w2 = d->t_w2; ca.t_b2 = d->t_b2; ca.c_w = d->c_w; ca.c_b = d->c_b;
+    ca.table = d->table; ca.cond = cond; ca.cond_kind = d->cfg.cond; ca.cond_dim = d->cfg.cond_dim; ca.D = D;
+    ca.slots = rows; ca.map = map;
+    ca.act_f32 = d->cact32 + (size_t)row0 * D;
+    ca.act_bf16 = d->bf16 ? (bf16_t*)d->cact + (size_t)row0 * D : nullptr;
+    ca.scratch = d->cscratch + (size_t)row0 * (kTFreq + 3 * D);
+    {
+        ProfScope ps(d, st, DRF_PROF_ELEMWISE, 4.0 * rows * ((double)kTFreq * D + (double)D * D));
+        if ((rc = launch_cond_embed(ca, st)) != DRF_OK) return rc;
+    }
+    const void* A = d->bf16 ? (const void*)ca.act_bf16 : (const void*)ca.act_f32;
+    return gemm(d, A, d->ada, rows, epi_store(mod_out, d->n_mod, true), st);
+}
+
+// The batched forward.  mod: this pass's rows of the modulation table (see conditioning()).
+drf_status forward(drf_denoiser* d, const float* x, const SlotMap& map, const float* mod, int slots, int n_blocks,
                    float* eps_out, float* resid_out, hipStream_t st)
 {
     const DitDims& dm = d->dm;
@@ -241,20 +279,6 @@ drf_status forward(drf_denoiser* d, const float* x, const SlotMap& map, const vo
     const bool f32 = !d->bf16;
     drf_status rc;
     if ((rc = ensure_workspace(d, slots, st)) != DRF_OK) return rc;
-
-    {   // conditioning: c per slot, then every block's shift/scale/gate in one GEMM
-        CondArgs ca{};
-        ca.t_w1 = d->t_w1; ca.t_b1 = d->t_b1; ca.t_w2 = d->t_w2; ca.t_b2 = d->t_b2; ca.c_w = d->c_w; ca.c_b = d->c_b;
-        ca.table = d->table; ca.cond = cond; ca.cond_kind = d->cfg.cond; ca.cond_dim = d->cfg.cond_dim; ca.D = D;
-        ca.slots = slots; ca.map = map; ca.act_f32 = d->cact32; ca.act_bf16 = d->bf16 ? (bf16_t*)d->cact : nullptr;
-        ca.scratch = d->cscratch;
-        {
-            ProfScope ps(d, st, DRF_PROF_ELEMWISE, 4.0 * slots * ((double)kTFreq * D + (double)D * D));
-            if ((rc = launch_cond_embed(ca, st)) != DRF_OK) return rc;
-        }
-        const void* A = d->bf16 ? d->cact : (const void*)d->cact32;
-        if ((rc = gemm(d, A, d->ada, slots, epi_store(d->mod, nm, true), st)) != DRF_OK) return rc;
-    }
     {
         ProfScope ps(d, st, DRF_PROF_ELEMWISE, (double)M * D * 8.0 + (double)M * dm.P * 4.0);
         if ((rc = launch_patch_embed(x, map, d->patch_w, d->patch_b, d->pos, dm, slots, d->resid, st)) != DRF_OK) return rc;
@@ -263,7 +287,7 @@ drf_status forward(drf_denoiser* d, const float* x, const SlotMap& map, const vo
     const size_t act = f32 ? 4 : 2;
     for (int l = 0; l < n_blocks; ++l) {
         const BlockW& b = d->blk[l];
-        const float* mrow = d->mod + (size_t)l * 6 * D;     // shift1 | scale1 | gate1 | shift2 | scale2 | gate2
+        const float* mrow = mod + (size_t)l * 6 * D;        // shift1 | scale1 | gate1 | shift2 | scale2 | gate2
         {
             ProfScope ps(d, st, DRF_PROF_ELEMWISE, ln_bytes);
             if ((rc = launch_ln_modulate(d->resid, mrow, mrow + D, nm, dm.T, M, D, d->hbuf, f32, st)) != DRF_OK) return rc;
@@ -318,7 +342,7 @@ drf_status forward(drf_denoiser* d, const float* x, const SlotMap& map, const vo
         DRF_HIP(hipMemcpyAsync(resid_out, d->resid, (size_t)M * D * 4, hipMemcpyDeviceToDevice, st));
         return DRF_OK;
     }
-    const float* fm = d->mod + (size_t)dm.L * 6 * D;        // final shift | scale
+    const float* fm = mod + (size_t)dm.L * 6 * D;           // final shift | scale
     ProfScope ps(d, st, DRF_PROF_ELEMWISE, (double)M * D * 4.0 + (double)M * dm.P * 4.0);
     return launch_final(d->resid, fm, fm + D, nm, d->fin_w, d->fin_b, dm, slots, eps_out, st);
 }
@@ -340,7 +364,10 @@ drf_status eps_common(drf_denoiser* den, const float* x, const int32_t* t, const
     if ((size_t)slots * den->dm.T > (size_t)1 << 30) DRF_FAIL(DRF_EINVAL, "slots * tokens too large");
     drf_status rc;
     if (den->cfg.cond == DRF_COND_TEXT && (rc = compute_ctx_kv(den, (const float*)cond, slots, st)) != DRF_OK) return rc;
-    return forward(den, x, identity_map(t), cond, slots, n_blocks, eps_out, resid_out, st);
+    const SlotMap map = identity_map(t);
+    if ((rc = ensure_cond(den, slots, st)) != DRF_OK) return rc;
+    if ((rc = conditioning(den, map, cond, slots, 0, den->mod, st)) != DRF_OK) return rc;
+    return forward(den, x, map, den->mod, slots, n_blocks, eps_out, resid_out, st);
 }
 
 }  // namespace
@@ -483,7 +510,8 @@ extern "C" void drf_denoiser_destroy(drf_denoiser* den)
 extern "C" drf_status drf_denoiser_reserve(drf_denoiser* den, int max_slots)
 {
     if (!den || max_slots < 0) DRF_FAIL(DRF_EINVAL, "bad argument");
-    return ensure_workspace(den, max_slots, nullptr);
+    drf_status rc = ensure_workspace(den, max_slots, nullptr);
+    return rc != DRF_OK ? rc : ensure_cond(den, max_slots, nullptr);
 }
 
 extern "C" drf_status drf_eps_batched(drf_denoiser* den, const float* x, const int32_t* t, const void* cond, int slots,
@@ -553,14 +581,41 @@ extern "C" drf_status drf_sample(drf_denoiser* den, const drf_sched_config* sche
     // cross-attention K/V depend only on the context: once per call, for the g*B distinct rows
     if (den->cfg.cond == DRF_COND_TEXT && (rc = compute_ctx_kv(den, (const float*)den->cond_cat, gB, st)) != DRF_OK) return rc;
 
+    // The conditioning of every pass is known up front (timesteps from the plan, per-sample
+    // cond rows): all modulation rows of the call are produced by a few large launches instead of
+    // one small, weight-bandwidth-bound GEMM per pass.  Rows are laid out pass after pass.
+    size_t total_groups = 0;
+    for (const Pass& p : passes) total_groups += p.eval_s.size();
+    if (total_groups * gB > (size_t)1 << 24) DRF_FAIL(DRF_EINVAL, "steps * batch too large");
+    if ((rc = ensure_cond(den, (int)(total_groups * gB), st)) != DRF_OK) return rc;
+    {
+        SlotMap map{};
+        map.t_dev = nullptr; map.group = gB; map.x_group = 1; map.x_batch = 1; map.cond_mod = gB;
+        int ng = 0, row0 = 0;
+        auto flush = [&]() -> drf_status {
+            if (ng == 0) return DRF_OK;
+            drf_status r = conditioning(den, map, den->cond_cat, ng * gB, row0, den->mod + (size_t)row0 * den->n_mod, st);
+            row0 += ng * gB; ng = 0;
+            return r;
+        };
+        for (const Pass& p : passes)
+            for (int s_eval : p.eval_s) {
+                map.taus[ng++] = sch.tau(s_eval);
+                if (ng == kMaxBlock && (rc = flush()) != DRF_OK) return rc;
+            }
+        if ((rc = flush()) != DRF_OK) return rc;
+    }
+
     const float* x_anchor = x_T;                    // state the next stand-alone pass evaluates
+    size_t mod_row = 0;
     for (const Pass& p : passes) {
         const int groups = (int)p.eval_s.size();
         SlotMap map{};
         map.t_dev = nullptr; map.group = gB; map.x_group = gB; map.x_batch = batch; map.cond_mod = gB;
         for (int i = 0; i < groups; ++i) map.taus[i] = sch.tau(p.eval_s[(size_t)i]);
         const float* xin = p.solo ? x_anchor : den->drafts;
-        if ((rc = forward(den, xin, map, den->cond_cat, groups * gB, dm.L, den->epsbuf, nullptr, st)) != DRF_OK) return rc;
+        if ((rc = forward(den, xin, map, den->mod + mod_row * den->n_mod, groups * gB, dm.L, den->epsbuf, nullptr, st)) != DRF_OK) return rc;
+        mod_row += (size_t)groups * gB;
 
         UpdateArgs u{};
         u.x_base = p.base_is_draft ? den->drafts : x_anchor;

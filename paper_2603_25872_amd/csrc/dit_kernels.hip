@@ -211,7 +211,7 @@ __global__ void __launch_bounds__(256) ln_modulate_kernel(const float* __restric
 // Final layer: LN + modulate, Linear(D -> P), scatter to [C][H][W].  A block of 4 waves takes
 // kFinalRowsPerBlock token rows; wave w keeps the weights of outputs w, w+4, w+8, w+12 (of each
 // group of 16) in registers and sweeps the rows, so nothing but the residual rows is re-read.
-constexpr int kFinalRowsPerBlock = 64;
+constexpr int kFinalRowsPerBlock = 16;
 template <int PER>
 __global__ void __launch_bounds__(256) final_kernel(const float* __restrict__ resid, const float* __restrict__ shift,
                                                     const float* __restrict__ scale, int mod_ld,
