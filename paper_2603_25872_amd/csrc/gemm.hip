@@ -1,6 +1,8 @@
 // GEMM C[M][N] = A[M][K] . W[N][K]^T with fused epilogues (bias, GELU-tanh, gated
 // residual).  bf16 path: MFMA 32x32x16 tiles fed from LDS, fp32 accumulate.
 // fp32 path: plain LDS-tiled FMA kernel for the fp32 configuration.
+#include <type_traits>
+
 #include "common.h"
 
 namespace drf {
@@ -305,86 +307,114 @@ gemm_bf16_xl_kernel(const bf16_t* __restrict__ A, const bf16_t* __restrict__ W, 
     constexpr int WBYTES = (NS * STAGE * 2 - PART) / NWT / 16 * 16; // this wave's private slice of the stages
     unsigned char* wbuf = smem_raw + PART + wl * WBYTES;
     const int mw = m0 + wm * TM, nw = n0 + wn * TN;
-    const bool resid = e.mode == EPI_RESID;
-    if (resid || e.out_f32) {
+    // bias of this lane's columns, fetched in one batch
+    float4 bb[NI];
+#pragma unroll
+    for (int i = 0; i < NI; ++i) {
+        const int n = nw + i * 16 + 4 * quarter;
+        bb[i] = *reinterpret_cast<const float4*>(e.bias + (n < N ? n : 0));
+    }
+    if (e.mode == EPI_RESID || e.out_f32) {
         constexpr int ROWB = TN * 4 + ((TN * 4) % 128 == 0 ? 16 : 0);
         constexpr int RPP = (WBYTES / ROWB) / 16 * 16 < TM ? (WBYTES / ROWB) / 16 * 16 : TM;   // rows per pass
         static_assert(RPP >= 16, "LDS slice too small for the fp32 epilogue");
-        constexpr int CH = TN / 4;                                  // float4 chunks per row
+        constexpr int CH = TN / 4, IT = (RPP * CH + 63) / 64;       // float4 chunks per row, chunks per lane and pass
+        auto run = [&](auto mode_c) {
+            constexpr int MODE = decltype(mode_c)::value;
 #pragma unroll
-        for (int j0 = 0; j0 < MI; j0 += RPP / 16) {
+            for (int j0 = 0; j0 < MI; j0 += RPP / 16) {
 #pragma unroll
-            for (int jj = 0; jj < RPP / 16; ++jj) {
-                const int j = j0 + jj;
-                if (j < MI) {
+                for (int jj = 0; jj < RPP / 16; ++jj) {
+                    const int j = j0 + jj;
+                    if (j < MI) {
 #pragma unroll
-                    for (int i = 0; i < NI; ++i) {
-                        const int n = nw + i * 16 + 4 * quarter;
-                        const int nc = n < N ? n : 0;
-                        const float4 bb = *reinterpret_cast<const float4*>(e.bias + nc);
-                        float4 v = make_float4(acc[i][j][0] + bb.x, acc[i][j][1] + bb.y, acc[i][j][2] + bb.z, acc[i][j][3] + bb.w);
-                        if (e.mode == EPI_STORE_GELU) { v.x = gelu_tanh(v.x); v.y = gelu_tanh(v.y); v.z = gelu_tanh(v.z); v.w = gelu_tanh(v.w); }
-                        *reinterpret_cast<float4*>(wbuf + (jj * 16 + l16) * ROWB + (i * 16 + 4 * quarter) * 4) = v;
-                    }
-                }
-            }
-            // rows back out, CH float4 chunks each
-            for (int id = lane; id < RPP * CH; id += 64) {
-                const int rl = id / CH, c = id % CH;
-                const int m = mw + j0 * 16 + rl, n = nw + c * 4;
-                if (j0 * 16 + rl < TM && m < M && n < N) {
-                    const float4 v = *reinterpret_cast<const float4*>(wbuf + rl * ROWB + c * 16);
-                    float4* xp = reinterpret_cast<float4*>((float*)e.out + (size_t)m * e.ldo + n);
-                    if (resid) {
-                        float4 x = *xp;
-                        if (e.gate) {
-                            const float4 g = *reinterpret_cast<const float4*>(e.gate + (size_t)fast_div(m, e.rps_magic, e.rps_shift) * e.gate_ld + n);
-                            x.x = fmaf(g.x, v.x, x.x); x.y = fmaf(g.y, v.y, x.y); x.z = fmaf(g.z, v.z, x.z); x.w = fmaf(g.w, v.w, x.w);
-                        } else {
-                            x.x += v.x; x.y += v.y; x.z += v.z; x.w += v.w;
+                        for (int i = 0; i < NI; ++i) {
+                            float4 v = make_float4(acc[i][j][0] + bb[i].x, acc[i][j][1] + bb[i].y, acc[i][j][2] + bb[i].z,
+                                                   acc[i][j][3] + bb[i].w);
+                            if (MODE == EPI_STORE_GELU) { v.x = gelu_tanh(v.x); v.y = gelu_tanh(v.y); v.z = gelu_tanh(v.z); v.w = gelu_tanh(v.w); }
+                            *reinterpret_cast<float4*>(wbuf + (jj * 16 + l16) * ROWB + (i * 16 + 4 * quarter) * 4) = v;
                         }
-                        *xp = x;
-                    } else {
-                        *xp = v;
+                    }
+                }
+                // rows back out, kBatch chunks per lane at a time: their loads are all issued before
+                // the first dependent store
+                constexpr int kBatch = 3;
+#pragma unroll
+                for (int it0 = 0; it0 < IT; it0 += kBatch) {
+                    float4 vv[kBatch], xx[kBatch], gg[kBatch];
+                    bool ok[kBatch];
+#pragma unroll
+                    for (int u = 0; u < kBatch; ++u) {
+                        const int id = lane + (it0 + u) * 64, rl = id / CH, c = id % CH;
+                        const int m = mw + j0 * 16 + rl, n = nw + c * 4;
+                        ok[u] = it0 + u < IT && id < RPP * CH && j0 * 16 + rl < TM && m < M && n < N;
+                        if (ok[u]) {
+                            vv[u] = *reinterpret_cast<const float4*>(wbuf + rl * ROWB + c * 16);
+                            if (MODE == EPI_RESID) {
+                                xx[u] = *reinterpret_cast<const float4*>((const float*)e.out + (size_t)m * e.ldo + n);
+                                gg[u] = e.gate ? *reinterpret_cast<const float4*>(e.gate + (size_t)fast_div(m, e.rps_magic, e.rps_shift) * e.gate_ld + n)
+                                               : make_float4(1.f, 1.f, 1.f, 1.f);
+                            }
+                        }
+                    }
+#pragma unroll
+                    for (int u = 0; u < kBatch; ++u) {
+                        const int id = lane + (it0 + u) * 64, rl = id / CH, c = id % CH;
+                        const int m = mw + j0 * 16 + rl, n = nw + c * 4;
+                        if (ok[u]) {
+                            float4 o = vv[u];
+                            if (MODE == EPI_RESID) {
+                                o.x = fmaf(gg[u].x, vv[u].x, xx[u].x); o.y = fmaf(gg[u].y, vv[u].y, xx[u].y);
+                                o.z = fmaf(gg[u].z, vv[u].z, xx[u].z); o.w = fmaf(gg[u].w, vv[u].w, xx[u].w);
+                            }
+                            *reinterpret_cast<float4*>((float*)e.out + (size_t)m * e.ldo + n) = o;
+                        }
                     }
                 }
             }
-        }
+        };
+        if (e.mode == EPI_RESID) run(std::integral_constant<int, EPI_RESID>{});
+        else if (e.mode == EPI_STORE_GELU) run(std::integral_constant<int, EPI_STORE_GELU>{});
+        else run(std::integral_constant<int, EPI_STORE>{});
     } else {
         constexpr int ROWB = TN * 2 + ((TN * 2) % 128 == 0 ? 16 : 0);
         constexpr int RPP = (WBYTES / ROWB) / 16 * 16 < TM ? (WBYTES / ROWB) / 16 * 16 : TM;
         static_assert(RPP >= 16, "LDS slice too small for the bf16 epilogue");
-        constexpr int CH = TN / 8;                                  // 16-byte chunks per row
+        constexpr int CH = TN / 8, IT = (RPP * CH + 63) / 64;       // 16-byte chunks per row, chunks per lane and pass
+        auto run = [&](auto mode_c) {
+            constexpr int MODE = decltype(mode_c)::value;
 #pragma unroll
-        for (int j0 = 0; j0 < MI; j0 += RPP / 16) {
+            for (int j0 = 0; j0 < MI; j0 += RPP / 16) {
 #pragma unroll
-            for (int jj = 0; jj < RPP / 16; ++jj) {
-                const int j = j0 + jj;
-                if (j < MI) {
+                for (int jj = 0; jj < RPP / 16; ++jj) {
+                    const int j = j0 + jj;
+                    if (j < MI) {
 #pragma unroll
-                    for (int i = 0; i < NI; ++i) {
-                        const int n = nw + i * 16 + 4 * quarter;
-                        const int nc = n < N ? n : 0;
-                        const float4 bb = *reinterpret_cast<const float4*>(e.bias + nc);
-                        float v0 = acc[i][j][0] + bb.x, v1 = acc[i][j][1] + bb.y, v2 = acc[i][j][2] + bb.z, v3 = acc[i][j][3] + bb.w;
-                        if (e.mode == EPI_STORE_GELU) { v0 = gelu_tanh(v0); v1 = gelu_tanh(v1); v2 = gelu_tanh(v2); v3 = gelu_tanh(v3); }
-                        bf16x4 o = { (bf16_t)v0, (bf16_t)v1, (bf16_t)v2, (bf16_t)v3 };
-                        *reinterpret_cast<bf16x4*>(wbuf + (jj * 16 + l16) * ROWB + (i * 16 + 4 * quarter) * 2) = o;
+                        for (int i = 0; i < NI; ++i) {
+                            float v0 = acc[i][j][0] + bb[i].x, v1 = acc[i][j][1] + bb[i].y, v2 = acc[i][j][2] + bb[i].z, v3 = acc[i][j][3] + bb[i].w;
+                            if (MODE == EPI_STORE_GELU) { v0 = gelu_tanh(v0); v1 = gelu_tanh(v1); v2 = gelu_tanh(v2); v3 = gelu_tanh(v3); }
+                            bf16x4 o = { (bf16_t)v0, (bf16_t)v1, (bf16_t)v2, (bf16_t)v3 };
+                            *reinterpret_cast<bf16x4*>(wbuf + (jj * 16 + l16) * ROWB + (i * 16 + 4 * quarter) * 2) = o;
+                        }
+                    }
+                }
+#pragma unroll
+                for (int it = 0; it < IT; ++it) {
+                    const int id = lane + it * 64, rl = id / CH, c = id % CH;
+                    const int m = mw + j0 * 16 + rl, n = nw + c * 8;
+                    if (id < RPP * CH && j0 * 16 + rl < TM && m < M && n < N) {
+                        const size_t off = MODE == EPI_STORE_HEADS ? heads_offset(e, m, n) : (size_t)m * e.ldo + n;
+                        if (n + 8 <= N)
+                            *reinterpret_cast<bf16x8*>((bf16_t*)e.out + off) = *reinterpret_cast<const bf16x8*>(wbuf + rl * ROWB + c * 16);
+                        else                // N is a multiple of 4: the last chunk of a row may be half valid
+                            *reinterpret_cast<bf16x4*>((bf16_t*)e.out + off) = *reinterpret_cast<const bf16x4*>(wbuf + rl * ROWB + c * 16);
                     }
                 }
             }
-            for (int id = lane; id < RPP * CH; id += 64) {
-                const int rl = id / CH, c = id % CH;
-                const int m = mw + j0 * 16 + rl, n = nw + c * 8;
-                if (j0 * 16 + rl < TM && m < M && n < N) {
-                    const size_t off = e.mode == EPI_STORE_HEADS ? heads_offset(e, m, n) : (size_t)m * e.ldo + n;
-                    if (n + 8 <= N)
-                        *reinterpret_cast<bf16x8*>((bf16_t*)e.out + off) = *reinterpret_cast<const bf16x8*>(wbuf + rl * ROWB + c * 16);
-                    else                    // N is a multiple of 4: the last chunk of a row may be half valid
-                        *reinterpret_cast<bf16x4*>((bf16_t*)e.out + off) = *reinterpret_cast<const bf16x4*>(wbuf + rl * ROWB + c * 16);
-                }
-            }
-        }
+        };
+        if (e.mode == EPI_STORE_GELU) run(std::integral_constant<int, EPI_STORE_GELU>{});
+        else if (e.mode == EPI_STORE_HEADS) run(std::integral_constant<int, EPI_STORE_HEADS>{});
+        else run(std::integral_constant<int, EPI_STORE>{});
     }
 }
 
