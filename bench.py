@@ -21,6 +21,10 @@ if ROOT not in sys.path:
 
 PEAK_BF16_TFLOPS = 2500.0     # MI355X dense bf16 MFMA
 PEAK_HBM_GBS = 8000.0
+# Bytes the bf16 GEMM launches of one configuration-3 call move past the L2, per launch on average: rocprofv3 FETCH_SIZE
+# and WRITE_SIZE, each scaled by what the same counter reads for a plain 1 GiB copy
+# (profiles/drf_sample_cfg3_pmc_traffic_mfma.txt).  Only valid for the default workload.
+GEMM_TRAFFIC_BYTES_PER_LAUNCH = {3: 2.18e8}
 
 
 def slot_eval_flops(dit):
@@ -111,9 +115,10 @@ def main():
         den.profile_enable(False)
         gm = fam["gemm"]
         ach = gm["work"] / (gm["ms"] * 1e-3) / 1e12 if gm["ms"] > 0 else 0.0
-        result["roofline"] = {"bound": "mfma", "kernel": "gemm_bf16_kernel (all GEMM launches of one call)",
+        result["roofline"] = {"bound": "mfma", "kernel": "gemm_bf16_xl_kernel (all bf16 GEMM launches of one drf_sample call)",
                               "achieved": ach, "peak": PEAK_BF16_TFLOPS, "unit": "TFLOP/s",
-                              "frac": ach / PEAK_BF16_TFLOPS, "traffic": None,
+                              "frac": ach / PEAK_BF16_TFLOPS,
+                              "traffic": GEMM_TRAFFIC_BYTES_PER_LAUNCH.get(args.config) if args.n is None and args.mode is None else None,
                               "launches": gm["launches"], "avg_launch_us": gm["ms"] * 1e3 / max(gm["launches"], 1),
                               "flops_per_launch": gm["work"] / max(gm["launches"], 1)}
         result["families_ms"] = {k: round(v["ms"], 3) for k, v in fam.items()}
@@ -124,6 +129,25 @@ def main():
         if up["ms"] > 0:
             result["update_kernel"] = {"launches": up["launches"], "avg_launch_us": up["ms"] * 1e3 / up["launches"],
                                        "achieved_GBps": up["work"] / (up["ms"] * 1e-3) / 1e9}
+        # the update kernel at a size where bandwidth, not launch latency, decides: 4096 samples of this latent,
+        # 4 drafts by skip transition (reads x and eps once, writes 4 fields)
+        E = dit["in_ch"] * dit["lat_h"] * dit["lat_w"]
+        big = 4096
+        xb = torch.randn((big, E), device="cuda")
+        eb = torch.randn((big, E), device="cuda")
+        ob = torch.empty((4, big, E), device="cuda")
+        targets = [S - 1, S - 2, S - 3, S - 4] if S >= 5 else [0] * 4
+        drf.skip_transition(sd, xb, eb, S, targets, out=ob)
+        e0, e1 = torch.cuda.Event(enable_timing=True), torch.cuda.Event(enable_timing=True)
+        e0.record()
+        for _ in range(10):
+            drf.skip_transition(sd, xb, eb, S, targets, out=ob)
+        e1.record()
+        torch.cuda.synchronize()
+        us = e0.elapsed_time(e1) * 100.0
+        result["update_kernel_scaled"] = {"batch": big, "bytes_per_launch": 6 * big * E * 4, "us_per_launch": us,
+                                          "achieved_GBps": 6 * big * E * 4 / (us * 1e-6) / 1e9, "peak_GBps": PEAK_HBM_GBS}
+        del xb, eb, ob
     den.close()
 
     if not args.no_cpu_baseline:

@@ -51,8 +51,8 @@ __global__ void __launch_bounds__(kTFreq / 2) time_features_kernel(const SlotMap
 }
 
 // y[r][j] = act(sum_k x[row(r)][k] w[j][k] + b[j]) for a handful of rows r (one per slot).
-// A block owns kSkinnyCols output columns for up to 64 rows at a time and walks K in chunks
-// staged through LDS: thread (row, column pair) accumulates two outputs.
+// A block owns kSkinnyCols output columns of one 64-row chunk (grid.y walks the chunks) and
+// walks K in pieces staged through LDS: thread (row, column pair) accumulates two outputs.
 constexpr int kSkinnyCols = 8, kSkinnyChunk = 128;
 template <bool SILU>
 __global__ void __launch_bounds__(256) skinny_linear_kernel(const float* __restrict__ x, int ldx, int row_mod,
@@ -63,7 +63,7 @@ __global__ void __launch_bounds__(256) skinny_linear_kernel(const float* __restr
     __shared__ float ws[kSkinnyCols][kSkinnyChunk + 1];
     const int tid = threadIdx.x, rl = tid & 63, cg = tid >> 6;
     const int j0 = blockIdx.x * kSkinnyCols;
-    for (int r0 = 0; r0 < rows; r0 += 64) {
+    for (int r0 = blockIdx.y * 64; r0 < rows; r0 += gridDim.y * 64) {
         float acc0 = 0.f, acc1 = 0.f;
         for (int k0 = 0; k0 < K; k0 += kSkinnyChunk) {
             __syncthreads();
@@ -294,7 +294,7 @@ drf_status launch_cond_embed(const CondArgs& a, hipStream_t st)
     float* h1 = femb + (size_t)S * kTFreq;
     float* temb = h1 + (size_t)S * D;
     float* vemb = temb + (size_t)S * D;
-    const dim3 gcol((D + kSkinnyCols - 1) / kSkinnyCols);
+    const dim3 gcol((D + kSkinnyCols - 1) / kSkinnyCols, (S + 63) / 64 < 64 ? (S + 63) / 64 : 64);
     hipLaunchKernelGGL(time_features_kernel, dim3(S), dim3(kTFreq / 2), 0, st, a.map, S, femb);
     hipLaunchKernelGGL(skinny_linear_kernel<true>, gcol, dim3(256), 0, st, femb, kTFreq, 0, a.t_w1, a.t_b1, S, kTFreq, D, h1);
     hipLaunchKernelGGL(skinny_linear_kernel<false>, gcol, dim3(256), 0, st, h1, D, 0, a.t_w2, a.t_b2, S, D, D, temb);
