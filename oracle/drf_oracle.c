@@ -57,7 +57,12 @@ typedef struct {
     double beta_start;    /* linear betas */
     double beta_end;
     int steps;            /* S: number of sampling steps */
+    double eta;           /* DDIM: sigma_{t,k} = eta * (DDPM posterior std of the same jump) */
+    int sampler;          /* ORC_DDIM | ORC_DDPM | ORC_EULER */
+    double shift;         /* Euler: time shift of the sigma grid (1 = uniform) */
 } orc_sched;
+
+enum { ORC_DDIM = 0, ORC_DDPM = 1, ORC_EULER = 2 };
 
 /* Cumulative alpha (the paper's alpha_t) at training timestep j:
  * prod_{i<=j} (1 - beta_i), betas linear from beta_start to beta_end. */
@@ -77,6 +82,24 @@ void orc_alpha_bar(const orc_sched* sc, double* abar /* [train_steps] */)
 int orc_tau(const orc_sched* sc, int s)
 {
     return (s - 1) * (sc->train_steps / sc->steps);
+}
+
+/* Euler solvers: discretisation sigma_s, s = 0..S, of the ODE's time variable, from
+ * sigma_0 = 0 (data) to sigma_S = 1 (noise): uniform u = s/S, optionally warped by the
+ * usual time shift  sigma = shift u / (1 + (shift - 1) u). */
+double orc_sigma_at(const orc_sched* sc, int s)
+{
+    double u = (double)s / (double)sc->steps;
+    return sc->shift * u / (1.0 + (sc->shift - 1.0) * u);
+}
+
+/* Timestep fed to the network for sampling index s under the configured sampler.
+ * Euler: the network's time input is sigma scaled to the training range, rounded to
+ * the nearest integer timestep. */
+int orc_net_time(const orc_sched* sc, int s)
+{
+    if (sc->sampler == ORC_EULER) return (int)floor(orc_sigma_at(sc, s) * (double)sc->train_steps + 0.5);
+    return orc_tau(sc, s);
 }
 
 /* Cumulative alpha at sampling index s; index 0 is clean data (alpha = 1). */
@@ -99,6 +122,83 @@ void orc_skip(const real* x, const real* eps, double a_from, double a_to, size_t
         real x0_hat = (x[e] - sn_from * eps[e]) / sa_from;
         out[e] = sa_to * x0_hat + sn_to * eps[e];
     }
+}
+
+/* Variance of the Bayes posterior q(x_{t-k} | x_t, x_0) (Eq. ddpm_skip_reverse_detail),
+ * with a_from = alpha_t and a_to = alpha_{t-k}. */
+double orc_posterior_var(double a_from, double a_to)
+{
+    return (1.0 - a_from / a_to) * (1.0 - a_to) / (1.0 - a_from);
+}
+
+/* sigma_{t,k} of the stochastic DDIM skip: eta times the posterior standard deviation
+ * of the same jump (eta = 0 deterministic, eta = 1 the DDPM-induced variance). */
+double orc_sigma(double eta, double a_from, double a_to)
+{
+    return eta * sqrt(orc_posterior_var(a_from, a_to));
+}
+
+/* Eq. ddim_skip_reverse with sigma > 0, as the draft and refine lines of Algorithm 1
+ * print it: predicted x_0, the noise direction shrunk to sqrt(1 - a_to - sigma^2), and
+ * fresh noise z scaled by sigma.  z may be NULL when sigma == 0. */
+void orc_skip_eta(const real* x, const real* eps, const real* z, double a_from, double a_to,
+                  double sigma, size_t n, real* out)
+{
+    const real sa_from = (real)sqrt(a_from), sn_from = (real)sqrt(1.0 - a_from);
+    const real sa_to = (real)sqrt(a_to), dir = (real)sqrt(1.0 - a_to - sigma * sigma);
+    const real sg = (real)sigma;
+    for (size_t e = 0; e < n; ++e) {
+        real x0_hat = (x[e] - sn_from * eps[e]) / sa_from;
+        real v = sa_to * x0_hat + dir * eps[e];
+        if (z) v += sg * z[e];
+        out[e] = v;
+    }
+}
+
+/* DDPM skip transition (Eq. ddpm_skip_reverse, ddpm_skip_reverse_detail): a draw from the
+ * Bayes posterior q(x_{t-k} | x_t, x_0) with x_0 replaced by the prediction from
+ * (x_t, eps): mean mu', variance sigma_{t,k}^2.  z may be NULL when the variance is 0. */
+void orc_ddpm_skip(const real* x, const real* eps, const real* z, double a_from, double a_to,
+                   size_t n, real* out)
+{
+    const double ratio = a_from / a_to;                      /* alpha_t / alpha_{t-k} */
+    const real sa_from = (real)sqrt(a_from), sn_from = (real)sqrt(1.0 - a_from);
+    const real wx = (real)(sqrt(ratio) * (1.0 - a_to));      /* weight of x_t in mu' */
+    const real w0 = (real)(sqrt(a_to) * (1.0 - ratio));      /* weight of x_0 in mu' */
+    const real den = (real)(1.0 - a_from);
+    const real sd = (real)sqrt(orc_posterior_var(a_from, a_to));
+    for (size_t e = 0; e < n; ++e) {
+        real x0_hat = (x[e] - sn_from * eps[e]) / sa_from;
+        real v = (wx * x[e] + w0 * x0_hat) / den;
+        if (z) v += sd * z[e];
+        out[e] = v;
+    }
+}
+
+/* First-order Euler skip of the ODE dx/dsigma = v: one integration step of any length,
+ * x_to = x + (sigma_to - sigma_from) v. */
+void orc_euler_skip(const real* x, const real* v, double sig_from, double sig_to, size_t n, real* out)
+{
+    const real h = (real)(sig_to - sig_from);
+    for (size_t e = 0; e < n; ++e) out[e] = x[e] + h * v[e];
+}
+
+/* One transition s_from -> s_to of the configured sampler from the pair (x, net output);
+ * z is this transition's fresh standard-normal field, or NULL for none. */
+static void transition(const orc_sched* sc, const double* abar, const real* x, const real* net,
+                       const real* z, int s_from, int s_to, size_t n, real* out)
+{
+    if (sc->sampler == ORC_EULER) {
+        orc_euler_skip(x, net, orc_sigma_at(sc, s_from), orc_sigma_at(sc, s_to), n, out);
+        return;
+    }
+    const double a_from = orc_abar_at(sc, abar, s_from), a_to = orc_abar_at(sc, abar, s_to);
+    if (sc->sampler == ORC_DDPM)
+        orc_ddpm_skip(x, net, z, a_from, a_to, n, out);
+    else if (sc->eta == 0.0)
+        orc_skip(x, net, a_from, a_to, n, out);
+    else
+        orc_skip_eta(x, net, z, a_from, a_to, orc_sigma(sc->eta, a_from, a_to), n, out);
 }
 
 /* ---------------------------------------------------------------- scheduler */
@@ -133,20 +233,26 @@ static void plan_push(orc_plan* p, int round, int kind, int s_from, int s_to, in
 
 /* Draft-and-refine sampling.  Returns 0, or -1 on bad arguments.
  * fn may be NULL: then only the plan is produced (xT, x0 unused).
+ * z: fresh standard-normal fields [n_noise][batch * E] for the stochastic samplers, one per
+ * kind-1 row and one per kind-2 row of the plan, in plan order (the draws of the draft
+ * loop and of the refine loop of Algorithm 1 / 2); NULL = no noise term is added.
  * plan_rows may be NULL.  *n_rows receives the number of rows the plan has
  * (even when it exceeds cap). */
 int orc_sample(const orc_sched* sc, int mode, int n, int batch, size_t E, const real* xT,
-               orc_eps_fn fn, void* user, real* x0, int32_t* plan_rows, size_t cap,
+               const real* z, orc_eps_fn fn, void* user, real* x0, int32_t* plan_rows, size_t cap,
                size_t* n_rows)
 {
     if (!sc || n < 1 || sc->steps < 1 || sc->steps > sc->train_steps ||
-        (mode != ORC_CONSERVATIVE && mode != ORC_AGGRESSIVE))
+        (mode != ORC_CONSERVATIVE && mode != ORC_AGGRESSIVE) || sc->sampler < ORC_DDIM ||
+        sc->sampler > ORC_EULER)
         return -1;
     const int S = sc->steps;
     const size_t F = (size_t)batch * E;          /* one field: all samples at one index */
     double* abar = (double*)malloc(sizeof(double) * (size_t)sc->train_steps);
     orc_alpha_bar(sc, abar);
     orc_plan plan = { plan_rows, cap, 0 };
+    size_t zi = 0;                               /* next unused noise field */
+#define NEXT_Z() (z ? z + F * (zi++) : (zi++, (const real*)NULL))
 
     real *x = NULL, *eps = NULL, *drafts = NULL, *deps = NULL, *y = NULL;
     if (fn) {
@@ -161,22 +267,23 @@ int orc_sample(const orc_sched* sc, int mode, int n, int batch, size_t E, const 
     int s = S, round = 0;
     if (mode == ORC_AGGRESSIVE) {
         /* Algorithm 1: one evaluation at the start gives the first anchor noise. */
-        plan_push(&plan, round, 0, s, s, orc_tau(sc, s));
-        if (fn) fn(user, x, s, orc_tau(sc, s), eps);
+        plan_push(&plan, round, 0, s, s, orc_net_time(sc, s));
+        if (fn) fn(user, x, s, orc_net_time(sc, s), eps);
         ++round;
     }
     while (s > 0) {
         int m;
         if (mode == ORC_CONSERVATIVE) {
             /* Algorithm 2: stand-alone noise at every anchor. */
-            plan_push(&plan, round, 0, s, s, orc_tau(sc, s));
-            if (fn) fn(user, x, s, orc_tau(sc, s), eps);
+            plan_push(&plan, round, 0, s, s, orc_net_time(sc, s));
+            if (fn) fn(user, x, s, orc_net_time(sc, s), eps);
             ++round;
             m = n < s - 1 ? n : s - 1;           /* last block is cut short at index 0 */
             if (m == 0) {                        /* one step left: plain update 1 -> 0 */
                 plan_push(&plan, round - 1, 2, s, s - 1, -1);
+                const real* zf = NEXT_Z();
                 if (fn) {
-                    orc_skip(x, eps, orc_abar_at(sc, abar, s), orc_abar_at(sc, abar, s - 1), F, y);
+                    transition(sc, abar, x, eps, zf, s, s - 1, F, y);
                     memcpy(x, y, sizeof(real) * F);
                 }
                 s = 0;
@@ -193,11 +300,12 @@ int orc_sample(const orc_sched* sc, int mode, int n, int batch, size_t E, const 
         if (!has_eval) --round;
         for (int i = 1; i <= m; ++i) {
             int to = s - i;
-            int tau = to >= 1 ? orc_tau(sc, to) : -1;
+            int tau = to >= 1 ? orc_net_time(sc, to) : -1;
             plan_push(&plan, round, 1, s, to, tau);
+            const real* zf = NEXT_Z();
             if (fn) {
                 real* d = drafts + F * (size_t)(i - 1);
-                orc_skip(x, eps, orc_abar_at(sc, abar, s), orc_abar_at(sc, abar, to), F, d);
+                transition(sc, abar, x, eps, zf, s, to, F, d);
                 if (to >= 1) fn(user, d, to, tau, deps + F * (size_t)(i - 1));
             }
         }
@@ -207,9 +315,9 @@ int orc_sample(const orc_sched* sc, int mode, int n, int batch, size_t E, const 
         if (fn) memcpy(y, drafts, sizeof(real) * F);
         for (int i = 2; i <= last; ++i) {
             plan_push(&plan, round, 2, s - i + 1, s - i, -1);
+            const real* zf = NEXT_Z();
             if (fn) {
-                orc_skip(y, deps + F * (size_t)(i - 2), orc_abar_at(sc, abar, s - i + 1),
-                         orc_abar_at(sc, abar, s - i), F, x);
+                transition(sc, abar, y, deps + F * (size_t)(i - 2), zf, s - i + 1, s - i, F, x);
                 memcpy(y, x, sizeof(real) * F);
             }
         }
@@ -220,10 +328,66 @@ int orc_sample(const orc_sched* sc, int mode, int n, int batch, size_t E, const 
             memcpy(eps, deps + F * (size_t)(m - 1), sizeof(real) * F);
         ++round;
     }
+#undef NEXT_Z
     if (fn) memcpy(x0, x, sizeof(real) * F);
     if (n_rows) *n_rows = plan.n;
     free(abar); free(x); free(eps); free(y); free(drafts); free(deps);
     return 0;
+}
+
+/* Number of noise fields orc_sample consumes: the kind-1 plus kind-2 rows of the plan. */
+long orc_noise_count(const orc_sched* sc, int mode, int n)
+{
+    size_t rows = 0;
+    if (orc_sample(sc, mode, n, 0, 0, NULL, NULL, NULL, NULL, NULL, NULL, 0, &rows) != 0) return -1;
+    int32_t* tab = (int32_t*)malloc(sizeof(int32_t) * ORC_ROW * (rows ? rows : 1));
+    orc_sample(sc, mode, n, 0, 0, NULL, NULL, NULL, NULL, NULL, tab, rows, &rows);
+    long cnt = 0;
+    for (size_t r = 0; r < rows; ++r) cnt += tab[ORC_ROW * r + 1] != 0;
+    free(tab);
+    return cnt;
+}
+
+/* ------------------------------------------------- counter-based normal draws */
+
+/* Philox4x32 with 10 rounds (Salmon et al., "Parallel random numbers: as easy as 1, 2, 3",
+ * SC'11): counter c[4], key k[2] -> four 32-bit words. */
+void orc_philox4x32(const uint32_t ctr[4], const uint32_t key[2], uint32_t out[4])
+{
+    uint32_t c0 = ctr[0], c1 = ctr[1], c2 = ctr[2], c3 = ctr[3], k0 = key[0], k1 = key[1];
+    for (int r = 0; r < 10; ++r) {
+        uint64_t p0 = (uint64_t)0xD2511F53u * c0, p1 = (uint64_t)0xCD9E8D57u * c2;
+        uint32_t n0 = (uint32_t)(p1 >> 32) ^ c1 ^ k0;
+        uint32_t n1 = (uint32_t)p1;
+        uint32_t n2 = (uint32_t)(p0 >> 32) ^ c3 ^ k1;
+        uint32_t n3 = (uint32_t)p0;
+        c0 = n0; c1 = n1; c2 = n2; c3 = n3;
+        k0 += 0x9E3779B9u; k1 += 0xBB67AE85u;
+    }
+    out[0] = c0; out[1] = c1; out[2] = c2; out[3] = c3;
+}
+
+/* The library's noise stream: elements 4q .. 4q+3 of noise field f come from the Philox
+ * block with counter (q low, q high, f, 0) and key = the 64-bit seed.  Words (r0, r1)
+ * and (r2, r3) each give two normals by Box-Muller with u = (r >> 8 + 1/2) 2^-24 in (0,1):
+ * sqrt(-2 ln u_a) * (cos, sin)(2 pi u_b). */
+void orc_normal_fill(uint64_t seed, uint32_t field0, size_t n_fields, size_t F, real* out)
+{
+    const uint32_t key[2] = { (uint32_t)seed, (uint32_t)(seed >> 32) };
+    const double two_pi = 6.283185307179586476925286766559;
+    for (size_t f = 0; f < n_fields; ++f)
+        for (size_t q = 0; 4 * q < F; ++q) {
+            const uint32_t ctr[4] = { (uint32_t)q, (uint32_t)((uint64_t)q >> 32), field0 + (uint32_t)f, 0u };
+            uint32_t r[4];
+            orc_philox4x32(ctr, key, r);
+            double u[4];
+            for (int j = 0; j < 4; ++j) u[j] = ((double)(r[j] >> 8) + 0.5) / 16777216.0;
+            const double nrm[4] = { sqrt(-2.0 * log(u[0])) * cos(two_pi * u[1]),
+                                    sqrt(-2.0 * log(u[0])) * sin(two_pi * u[1]),
+                                    sqrt(-2.0 * log(u[2])) * cos(two_pi * u[3]),
+                                    sqrt(-2.0 * log(u[2])) * sin(two_pi * u[3]) };
+            for (int j = 0; j < 4 && 4 * q + (size_t)j < F; ++j) out[f * F + 4 * q + (size_t)j] = (real)nrm[j];
+        }
 }
 
 /* ------------------------------------------------------------- DiT denoiser */
@@ -578,14 +742,15 @@ static void dit_eps_fn(void* user, const real* x, int s, int tau, real* eps_out)
     free(t);
 }
 
-/* Whole path with the DiT as predictor.  null_cond == NULL: no guidance. */
+/* Whole path with the DiT as predictor.  null_cond == NULL: no guidance.
+ * z: noise fields as in orc_sample, or NULL. */
 int orc_sample_dit(const orc_dit_config* c, const real* weights, const orc_sched* sc, int mode,
-                   int n, int batch, const real* xT, const void* cond, const void* null_cond,
-                   double guidance, real* x0)
+                   int n, int batch, const real* xT, const real* z, const void* cond,
+                   const void* null_cond, double guidance, real* x0)
 {
     orc_dit_user u = { c, weights, cond, null_cond, guidance, batch };
     const size_t E = (size_t)c->in_ch * c->lat_h * c->lat_w;
-    return orc_sample(sc, mode, n, batch, E, xT, dit_eps_fn, &u, x0, NULL, 0, NULL);
+    return orc_sample(sc, mode, n, batch, E, xT, z, dit_eps_fn, &u, x0, NULL, 0, NULL);
 }
 
 /* One guided noise evaluation for a batch at a common training timestep. */

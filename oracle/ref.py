@@ -13,7 +13,7 @@ ROW = 5
 
 class Sched(C.Structure):
     _fields_ = [("train_steps", C.c_int), ("beta_start", C.c_double), ("beta_end", C.c_double),
-                ("steps", C.c_int)]
+                ("steps", C.c_int), ("eta", C.c_double), ("sampler", C.c_int), ("shift", C.c_double)]
 
 
 class DitConfig(C.Structure):
@@ -39,11 +39,23 @@ class Oracle:
         L.orc_abar_at.restype = C.c_double
         L.orc_skip.argtypes = [C.c_void_p, C.c_void_p, C.c_double, C.c_double, C.c_size_t, C.c_void_p]
         self.EPS_FN = C.CFUNCTYPE(None, C.c_void_p, C.c_void_p, C.c_int, C.c_int, C.c_void_p)
-        L.orc_sample.argtypes = [C.c_void_p, C.c_int, C.c_int, C.c_int, C.c_size_t, C.c_void_p,
+        L.orc_sample.argtypes = [C.c_void_p, C.c_int, C.c_int, C.c_int, C.c_size_t, C.c_void_p, C.c_void_p,
                                  C.c_void_p, C.c_void_p, C.c_void_p, C.c_void_p, C.c_size_t, C.c_void_p]
+        L.orc_sigma_at.restype = C.c_double
+        L.orc_posterior_var.restype = C.c_double
+        L.orc_posterior_var.argtypes = [C.c_double, C.c_double]
+        L.orc_sigma.restype = C.c_double
+        L.orc_sigma.argtypes = [C.c_double, C.c_double, C.c_double]
+        L.orc_skip_eta.argtypes = [C.c_void_p, C.c_void_p, C.c_void_p, C.c_double, C.c_double, C.c_double,
+                                   C.c_size_t, C.c_void_p]
+        L.orc_ddpm_skip.argtypes = [C.c_void_p, C.c_void_p, C.c_void_p, C.c_double, C.c_double, C.c_size_t,
+                                    C.c_void_p]
+        L.orc_euler_skip.argtypes = [C.c_void_p, C.c_void_p, C.c_double, C.c_double, C.c_size_t, C.c_void_p]
+        L.orc_noise_count.restype = C.c_long
+        L.orc_normal_fill.argtypes = [C.c_uint64, C.c_uint32, C.c_size_t, C.c_size_t, C.c_void_p]
         L.orc_dit_eps.argtypes = [C.c_void_p] * 5 + [C.c_int, C.c_void_p, C.c_int, C.c_void_p]
         L.orc_sample_dit.argtypes = [C.c_void_p, C.c_void_p, C.c_void_p, C.c_int, C.c_int, C.c_int,
-                                     C.c_void_p, C.c_void_p, C.c_void_p, C.c_double, C.c_void_p]
+                                     C.c_void_p, C.c_void_p, C.c_void_p, C.c_void_p, C.c_double, C.c_void_p]
         L.orc_eps_guided.argtypes = [C.c_void_p, C.c_void_p, C.c_void_p, C.c_int, C.c_void_p,
                                      C.c_void_p, C.c_double, C.c_int, C.c_void_p]
 
@@ -80,7 +92,8 @@ class Oracle:
     # ---- schedule
     @staticmethod
     def sched(d):
-        return Sched(d["train_steps"], d["beta_start"], d["beta_end"], d["steps"])
+        return Sched(d["train_steps"], d["beta_start"], d["beta_end"], d["steps"], float(d.get("eta", 0.0)),
+                     int(d.get("sampler", 0)), float(d.get("shift", 1.0)))
 
     def alpha_bar(self, sd):
         sc = self.sched(sd)
@@ -97,6 +110,14 @@ class Oracle:
         sc = self.sched(sd)
         return float(self.lib.orc_abar_at(C.byref(sc), _ptr(ab), C.c_int(s)))
 
+    def sigma_at(self, sd, s):
+        sc = self.sched(sd)
+        return float(self.lib.orc_sigma_at(C.byref(sc), C.c_int(s)))
+
+    def net_time(self, sd, s):
+        sc = self.sched(sd)
+        return int(self.lib.orc_net_time(C.byref(sc), C.c_int(s)))
+
     # ---- operator
     def skip(self, x, eps, a_from, a_to):
         x = np.ascontiguousarray(x, self.real)
@@ -105,22 +126,77 @@ class Oracle:
         self.lib.orc_skip(_ptr(x), _ptr(eps), a_from, a_to, x.size, _ptr(out))
         return out
 
+    def posterior_var(self, a_from, a_to):
+        return float(self.lib.orc_posterior_var(a_from, a_to))
+
+    def sigma(self, eta, a_from, a_to):
+        return float(self.lib.orc_sigma(eta, a_from, a_to))
+
+    def _z(self, z, like):
+        if z is None:
+            return None
+        z = np.ascontiguousarray(z, self.real)
+        return z
+
+    def skip_eta(self, x, eps, z, a_from, a_to, sigma):
+        x = np.ascontiguousarray(x, self.real)
+        eps = np.ascontiguousarray(eps, self.real)
+        z = self._z(z, x)
+        out = np.empty_like(x)
+        self.lib.orc_skip_eta(_ptr(x), _ptr(eps), _ptr(z), a_from, a_to, sigma, x.size, _ptr(out))
+        return out
+
+    def ddpm_skip(self, x, eps, z, a_from, a_to):
+        x = np.ascontiguousarray(x, self.real)
+        eps = np.ascontiguousarray(eps, self.real)
+        z = self._z(z, x)
+        out = np.empty_like(x)
+        self.lib.orc_ddpm_skip(_ptr(x), _ptr(eps), _ptr(z), a_from, a_to, x.size, _ptr(out))
+        return out
+
+    def euler_skip(self, x, v, sig_from, sig_to):
+        x = np.ascontiguousarray(x, self.real)
+        v = np.ascontiguousarray(v, self.real)
+        out = np.empty_like(x)
+        self.lib.orc_euler_skip(_ptr(x), _ptr(v), sig_from, sig_to, x.size, _ptr(out))
+        return out
+
+    # ---- noise stream
+    def philox(self, ctr, key):
+        c = (C.c_uint32 * 4)(*ctr)
+        k = (C.c_uint32 * 2)(*key)
+        o = (C.c_uint32 * 4)()
+        self.lib.orc_philox4x32(c, k, o)
+        return [int(v) for v in o]
+
+    def normal_fill(self, seed, field0, n_fields, F):
+        out = np.empty((n_fields, F), self.real)
+        self.lib.orc_normal_fill(C.c_uint64(seed), C.c_uint32(field0), n_fields, F, _ptr(out))
+        return out
+
+    def noise_count(self, sd, mode, n):
+        sc = self.sched(sd)
+        return int(self.lib.orc_noise_count(C.byref(sc), mode, n))
+
     # ---- scheduler
     def plan(self, sd, mode, n):
         sc = self.sched(sd)
         cnt = C.c_size_t(0)
-        rc = self.lib.orc_sample(C.byref(sc), mode, n, 0, 0, None, None, None, None, None, 0, C.byref(cnt))
+        rc = self.lib.orc_sample(C.byref(sc), mode, n, 0, 0, None, None, None, None, None, None, 0, C.byref(cnt))
         if rc != 0:
             raise ValueError("oracle rejected plan arguments")
         rows = np.zeros((cnt.value, ROW), np.int32)
-        self.lib.orc_sample(C.byref(sc), mode, n, 0, 0, None, None, None, None, _ptr(rows), cnt.value,
+        self.lib.orc_sample(C.byref(sc), mode, n, 0, 0, None, None, None, None, None, _ptr(rows), cnt.value,
                             C.byref(cnt))
         return rows
 
-    def sample_with(self, sd, mode, n, xT, eps_py):
+    def sample_with(self, sd, mode, n, xT, eps_py, z=None):
         """Run the scheduler with a Python noise predictor eps_py(x, s, tau) -> eps,
-        x shaped like xT ([batch, ...])."""
+        x shaped like xT ([batch, ...]); z: noise fields [n_noise, batch, ...] or None."""
         xT = np.ascontiguousarray(xT, self.real)
+        if z is not None:
+            z = np.ascontiguousarray(z, self.real)
+            assert z.shape[0] >= self.noise_count(sd, mode, n) and z[0].size == xT.size
         batch = xT.shape[0]
         E = xT.size // batch
         shape = xT.shape
@@ -134,7 +210,7 @@ class Oracle:
         fn = self.EPS_FN(cb)
         x0 = np.empty_like(xT)
         sc = self.sched(sd)
-        rc = self.lib.orc_sample(C.byref(sc), mode, n, batch, E, _ptr(xT), C.cast(fn, C.c_void_p), None,
+        rc = self.lib.orc_sample(C.byref(sc), mode, n, batch, E, _ptr(xT), _ptr(z), C.cast(fn, C.c_void_p), None,
                                  _ptr(x0), None, 0, None)
         if rc != 0:
             raise ValueError("oracle rejected sample arguments")
@@ -193,14 +269,17 @@ class Oracle:
                                 float(guidance or 0.0), x.shape[0], _ptr(out))
         return out
 
-    def sample_dit(self, d, w, sd, mode, n, xT, cond, null_cond=None, guidance=0.0):
+    def sample_dit(self, d, w, sd, mode, n, xT, cond, null_cond=None, guidance=0.0, z=None):
         cfg = self.dit_config(d)
         w = self.prepare_weights(w)
         xT = np.ascontiguousarray(xT, self.real)
         x0 = np.empty_like(xT)
         sc = self.sched(sd)
         cond, null_cond = self._cond(d, cond), self._cond(d, null_cond)
-        rc = self.lib.orc_sample_dit(C.byref(cfg), _ptr(w), C.byref(sc), mode, n, xT.shape[0], _ptr(xT),
+        if z is not None:
+            z = np.ascontiguousarray(z, self.real)
+            assert z.shape[0] >= self.noise_count(sd, mode, n) and z[0].size == xT.size
+        rc = self.lib.orc_sample_dit(C.byref(cfg), _ptr(w), C.byref(sc), mode, n, xT.shape[0], _ptr(xT), _ptr(z),
                                      _ptr(cond), _ptr(null_cond), float(guidance or 0.0), _ptr(x0))
         if rc != 0:
             raise ValueError("oracle rejected sample arguments")
