@@ -6,11 +6,12 @@
  * Ensure").  Its three building blocks are the calls below:
  *   - the noise predictor eps_theta(x, t), evaluated on k drafts at once
  *     (Algorithm 1, the "concurrently" loop): drf_eps_batched;
- *   - the skip transition x_{t-k} = Skip(x_t, eps_t) (Eq. ddim_skip_reverse):
- *     drf_skip_transition;
+ *   - the skip transition x_{t-k} = Skip(x_t, eps_t) (Eq. ddim_skip_reverse, with or
+ *     without variance; Eq. ddpm_skip_reverse; the Euler skip of the ODE solvers):
+ *     drf_skip_transition, drf_skip_transition_noise;
  *   - the standard denoising update that refines the drafts (Algorithm 1, second
  *     loop): drf_refine_step;
- * and drf_sample runs the whole draft-and-refine loop in either mode.
+ * and drf_sample / drf_sample_noise run the whole draft-and-refine loop in either mode.
  * On one GPU the paper's k devices are k groups of batch slots of one forward pass.
  *
  * Conventions
@@ -24,9 +25,12 @@
  *   - One denoiser handle may be used by one stream at a time.
  *
  * Indices.  Sampling indices s run S, S-1, ..., 1, 0 (the paper's t, with S the
- * paper's T).  The network is fed the training timestep tau_s = (s-1) *
+ * paper's T).  DDIM / DDPM: the network is fed the training timestep tau_s = (s-1) *
  * floor(train_steps / S) for s >= 1.  alpha-bar_s is the cumulative product of
  * (1 - beta) up to tau_s with linear betas; alpha-bar_0 = 1 (clean data).
+ * Euler: the ODE time of index s is sigma_s = shift u / (1 + (shift - 1) u), u = s/S
+ * (sigma_0 = 0 data, sigma_S = 1 noise), the network is a velocity predictor and is fed
+ * the integer time floor(sigma_s train_steps + 1/2).
  * The block size k of the paper is `n` here.
  *
  * The noise predictor is a latent DiT whose internals the paper does not fix;
@@ -50,12 +54,21 @@ typedef enum {
     DRF_ESHAPE = -2,        /* configuration the kernels cannot take (divisibility) */
     DRF_ENOMEM = -3,        /* device or host allocation failed */
     DRF_EHIP = -4,          /* a HIP runtime call failed */
-    DRF_EUNSUPPORTED = -5   /* valid in the paper, not built here (eta > 0) */
+    DRF_EUNSUPPORTED = -5   /* valid in the paper, not built here */
 } drf_status;
 
 typedef enum { DRF_CONSERVATIVE = 0, DRF_AGGRESSIVE = 1 } drf_mode;
 typedef enum { DRF_F32 = 0, DRF_BF16 = 1 } drf_dtype;
 typedef enum { DRF_COND_VECTOR = 0, DRF_COND_CLASS = 1, DRF_COND_TEXT = 2 } drf_cond_kind;
+/*
+ * Which skip transition the sampler uses (section "Skip Transitions"):
+ *   DRF_DDIM   Eq. ddim_skip_reverse with sigma_{t,k} = eta * (posterior std of the same jump);
+ *   DRF_DDPM   Eq. ddpm_skip_reverse: a draw from the Bayes posterior q(x_{t-k} | x_t, x_0_hat)
+ *              (mean mu', variance sigma_{t,k}^2 of Eq. ddpm_skip_reverse_detail); eta is ignored;
+ *   DRF_EULER  x_{t-k} = x_t + (sigma_{t-k} - sigma_t) v(x_t, sigma_t), the network output read as
+ *              the velocity v; no variance; beta_* and eta are ignored.
+ */
+typedef enum { DRF_DDIM = 0, DRF_DDPM = 1, DRF_EULER = 2 } drf_sampler;
 
 /*
  * The DiT (this build's definition; D = hidden, P = in_ch*patch^2, R = mlp_ratio,
@@ -93,8 +106,25 @@ typedef struct {
     int train_steps;            /* training timesteps of the beta schedule (1000) */
     double beta_start, beta_end;/* linear betas */
     int steps;                  /* S, 1 <= S <= train_steps */
-    double eta;                 /* must be 0: deterministic DDIM (Eq. ddim_skip_reverse, sigma = 0) */
+    double eta;                 /* DRF_DDIM: 0 <= eta <= 1; 0 = deterministic, 1 = DDPM-induced variance */
+    drf_sampler sampler;
+    double shift;               /* DRF_EULER: time shift of the sigma grid, > 0 (1 = uniform) */
 } drf_sched_config;
+
+/*
+ * Where the fresh standard-normal fields of a stochastic sampler come from (the draws
+ * "sample z" of Algorithm 1 / 2).  A field is one fp32 array [batch][elems_per_sample].
+ *   z != NULL: DEVICE fp32 [count][batch][elems_per_sample], explicit fields; the k-th field
+ *              a call consumes is z[k]; seed and field0 are ignored.
+ *   z == NULL: the k-th field is field number field0 + k of the library's counter-based
+ *              stream for `seed` (see drf_normal_fill), generated inside the update kernel
+ *              and never stored.
+ */
+typedef struct {
+    const float* z;
+    uint64_t seed;
+    uint32_t field0;
+} drf_noise;
 
 /*
  * Number of fp32 scalars in the flat parameter array.  Linear weights are [out][in]:
@@ -145,11 +175,13 @@ drf_status drf_eps_trace(drf_denoiser* den, const float* x, const int32_t* t, co
                          int slots, int n_blocks, float* resid_out, void* hip_stream);
 
 /*
- * DDIM skip transitions with zero variance (Eq. ddim_skip_reverse; the draft line of
- * Algorithm 1): for j < m,
+ * Skip transitions without a noise term.  DRF_DDIM with eta = 0 (Eq. ddim_skip_reverse,
+ * zero variance; the draft line of Algorithm 1): for j < m,
  *   x_to[j] = sqrt(ab_to/ab_from) x_from + (sqrt(1-ab_to) - sqrt(ab_to/ab_from) sqrt(1-ab_from)) eps_from
  * with ab_* the cumulative alpha at sampling indices s_from and s_to[j]; algebraically
  * the paper's predicted-x_0 form.  Coefficients are formed in double, applied in fp32.
+ * Other samplers: the same call applies their A x + B net form (see
+ * drf_skip_transition_noise) as long as no requested transition has variance.
  *   x_from, eps_from  DEVICE fp32 [batch][elems_per_sample]
  *   s_to              HOST int [m], each 0 <= s_to[j] <= S (any direction is allowed)
  *   x_to              DEVICE fp32 [m][batch][elems_per_sample]; must not alias the inputs
@@ -157,6 +189,33 @@ drf_status drf_eps_trace(drf_denoiser* den, const float* x, const int32_t* t, co
 drf_status drf_skip_transition(const drf_sched_config* sched, const float* x_from, const float* eps_from,
                                int s_from, const int* s_to, int m, int batch, size_t elems_per_sample,
                                float* x_to, void* hip_stream);
+
+/*
+ * Skip transitions of the configured sampler, variance included: for j < m,
+ *   x_to[j] = A_j x_from + B_j net_from + C_j z_j
+ * DRF_DDIM:  A = sqrt(ab_to/ab_from), B = sqrt(1 - ab_to - sigma^2) - A sqrt(1 - ab_from), C = sigma,
+ *            sigma = eta sqrt((1 - ab_from/ab_to)(1 - ab_to)/(1 - ab_from))   (Eq. ddim_skip_reverse);
+ * DRF_DDPM:  A x + B eps = mu'(x, x_0_hat), C = sigma_{t,k}          (Eq. ddpm_skip_reverse_detail);
+ * DRF_EULER: A = 1, B = sigma_to - sigma_from, C = 0.
+ * z_j is field j of `noise`.  noise may be NULL when every C_j is 0 (DRF_EULER, eta == 0, or
+ * all targets at index 0); otherwise that is DRF_EINVAL.  A transition with variance needs
+ * 1 <= s_from and s_to[j] <= s_from.  Other arguments as in drf_skip_transition, which is this
+ * call with noise == NULL.
+ */
+drf_status drf_skip_transition_noise(const drf_sched_config* sched, const float* x_from, const float* net_from,
+                                     int s_from, const int* s_to, int m, int batch, size_t elems_per_sample,
+                                     const drf_noise* noise, float* x_to, void* hip_stream);
+
+/*
+ * The library's noise stream, written out: elements 4q .. 4q+3 of field f are the four
+ * normals of the Philox4x32-10 block with counter (q low, q high, f, 0) and key
+ * (seed low, seed high); word pairs (r0, r1), (r2, r3) each give two normals by Box-Muller,
+ * sqrt(-2 ln u_a) (cos, sin)(2 pi u_b), u = ((r >> 9) + 1/2) 2^-23.
+ *   out  DEVICE fp32 [n_fields][field_elems], fields field0 .. field0 + n_fields - 1.
+ * A stochastic call with drf_noise.z == NULL uses exactly these values.
+ */
+drf_status drf_normal_fill(uint64_t seed, uint32_t field0, size_t n_fields, size_t field_elems, float* out,
+                           void* hip_stream);
 
 /*
  * The standard denoising update s_from -> s_from - 1 (Algorithm 1, refinement loop).
@@ -168,7 +227,7 @@ drf_status drf_refine_step(const drf_sched_config* sched, const float* x, const 
 
 /*
  * Draft-and-refine sampling, Algorithm 1 (DRF_AGGRESSIVE) or Algorithm 2
- * (DRF_CONSERVATIVE) with block size n; n = 1 is sequential DDIM in both modes.  The
+ * (DRF_CONSERVATIVE) with block size n; n = 1 is the sequential sampler in both modes.  The
  * last block is cut short at index 0 and a draft of x_0 is never fed to the network,
  * so exactly S predictor evaluations per sample are made.
  *   x_T        DEVICE fp32 [batch][in_ch][lat_h][lat_w]
@@ -182,6 +241,18 @@ drf_status drf_refine_step(const drf_sched_config* sched, const float* x, const 
 drf_status drf_sample(drf_denoiser* den, const drf_sched_config* sched, drf_mode mode, int n, int batch,
                       const float* x_T, const void* cond, const void* null_cond, float cfg_scale,
                       float* x_0_out, void* hip_stream);
+
+/*
+ * drf_sample with the draws of the stochastic samplers (eta > 0, DRF_DDPM): one fresh field
+ * per kind-1 row and per kind-2 row of the plan (see drf_plan_build), consumed in row order,
+ * also by rows whose transition has no variance (a step onto index 0).  drf_noise_count gives
+ * their number.  noise == NULL is allowed only when no transition has variance; drf_sample is
+ * this call with noise == NULL.
+ */
+drf_status drf_sample_noise(drf_denoiser* den, const drf_sched_config* sched, drf_mode mode, int n, int batch,
+                            const float* x_T, const void* cond, const void* null_cond, float cfg_scale,
+                            const drf_noise* noise, float* x_0_out, void* hip_stream);
+drf_status drf_noise_count(const drf_sched_config* sched, drf_mode mode, int n, size_t* count);
 
 /*
  * The bookkeeping of drf_sample as a table (host only, no GPU needed).  Rows of

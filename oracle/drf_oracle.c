@@ -369,7 +369,8 @@ void orc_philox4x32(const uint32_t ctr[4], const uint32_t key[2], uint32_t out[4
 
 /* The library's noise stream: elements 4q .. 4q+3 of noise field f come from the Philox
  * block with counter (q low, q high, f, 0) and key = the 64-bit seed.  Words (r0, r1)
- * and (r2, r3) each give two normals by Box-Muller with u = (r >> 8 + 1/2) 2^-24 in (0,1):
+ * and (r2, r3) each give two normals by Box-Muller with u = ((r >> 9) + 1/2) 2^-23 in (0,1)
+ * (24 significant bits: the same number in single and double precision):
  * sqrt(-2 ln u_a) * (cos, sin)(2 pi u_b). */
 void orc_normal_fill(uint64_t seed, uint32_t field0, size_t n_fields, size_t F, real* out)
 {
@@ -381,7 +382,7 @@ void orc_normal_fill(uint64_t seed, uint32_t field0, size_t n_fields, size_t F, 
             uint32_t r[4];
             orc_philox4x32(ctr, key, r);
             double u[4];
-            for (int j = 0; j < 4; ++j) u[j] = ((double)(r[j] >> 8) + 0.5) / 16777216.0;
+            for (int j = 0; j < 4; ++j) u[j] = ((double)(r[j] >> 9) + 0.5) / 8388608.0;
             const double nrm[4] = { sqrt(-2.0 * log(u[0])) * cos(two_pi * u[1]),
                                     sqrt(-2.0 * log(u[0])) * sin(two_pi * u[1]),
                                     sqrt(-2.0 * log(u[2])) * cos(two_pi * u[3]),

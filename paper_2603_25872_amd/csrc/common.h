@@ -20,11 +20,19 @@ void set_error(const char* fmt, ...);
 // ---- schedule / plan (host) ---------------------------------------------------
 struct Schedule {
     std::vector<double> abar;   // cumulative alpha per training timestep
-    int steps = 0, stride = 0;
+    int steps = 0, stride = 0, train_steps = 0;
+    drf_sampler sampler = DRF_DDIM;
+    double eta = 0.0, shift = 1.0;
     int tau(int s) const { return (s - 1) * stride; }
     double abar_at(int s) const { return s == 0 ? 1.0 : abar[(size_t)tau(s)]; }
-    // x_to = A x_from + B eps
-    void coef(int s_from, int s_to, float* A, float* B) const;
+    // Euler: ODE time of sampling index s
+    double sigma_at(int s) const;
+    // integer time fed to the network at sampling index s >= 1
+    int net_time(int s) const;
+    // true when some transition of this sampler adds fresh noise
+    bool stochastic() const { return sampler == DRF_DDPM || (sampler == DRF_DDIM && eta != 0.0); }
+    // x_to = A x_from + B net + C z.  Fails for a transition with variance that is not a move towards data.
+    drf_status coef(int s_from, int s_to, float* A, float* B, float* C) const;
 };
 drf_status make_schedule(const drf_sched_config* sc, Schedule* out);
 
@@ -36,14 +44,17 @@ struct Pass {
     std::vector<int> eval_s;        // sampling indices evaluated, one per slot group
     bool base_is_draft = false;     // chain starts from the first draft, else from the anchor state
     std::vector<std::pair<int, int>> chain;   // standard updates (s_from -> s_to); update i uses noise field i
+    std::vector<int> chain_z;       // per update: ordinal of its fresh-noise field among the call's draws
     int anchor_field = -1;          // noise field that pairs with the state after the chain (-1: none)
     std::vector<int> draft_to;      // skip targets drafted from (state after chain, anchor noise)
+    std::vector<int> draft_z;       // per draft: ordinal of its fresh-noise field
     int s_after = 0;                // index of the state after the chain
     bool writes_x0 = false;         // the state after the chain (or the lone draft to 0) is x_0
 };
-// rows: plan table in the documented row format (may be NULL).
+// rows: plan table in the documented row format (may be NULL).  n_noise (may be NULL): number of
+// fresh-noise fields the call draws (kind-1 plus kind-2 rows).
 drf_status build_plan(const Schedule& sch, drf_mode mode, int n, std::vector<Pass>* passes,
-                      std::vector<int32_t>* rows);
+                      std::vector<int32_t>* rows, size_t* n_noise = nullptr);
 
 // ---- elementwise update kernel --------------------------------------------------
 constexpr int kMaxBlock = 64;       // largest block size n the update kernel's argument block holds
@@ -57,7 +68,18 @@ struct UpdateArgs {
     float w;               // guidance scale
     int n_chain, anchor_field, n_draft;
     float cA[kMaxBlock], cB[kMaxBlock], dA[kMaxBlock], dB[kMaxBlock];
+    // fresh noise: y += cC[i] * z(field cz[i]) after chain update i, d_j += dC[j] * z(field dz[j]);
+    // a zero coefficient means the field is not touched
+    int noise_mode;        // 0 none | 1 explicit fields at z | 2 generated from (seed, z_field0 + ordinal)
+    const float* z;        // [..][field]
+    uint64_t seed;
+    uint32_t z_field0;
+    float cC[kMaxBlock], dC[kMaxBlock];
+    int cz[kMaxBlock], dz[kMaxBlock];
 };
+enum { NOISE_NONE = 0, NOISE_EXPLICIT = 1, NOISE_PHILOX = 2 };
+// Fills noise_mode / z / seed / z_field0 from the caller's source; fails when a nonzero cC / dC has no source.
+drf_status set_noise_source(UpdateArgs* a, const drf_noise* noise);
 drf_status launch_update(const UpdateArgs& a, hipStream_t st);
 
 // ---- DiT kernels ------------------------------------------------------------------

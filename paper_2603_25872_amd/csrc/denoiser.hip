@@ -534,6 +534,13 @@ extern "C" drf_status drf_sample(drf_denoiser* den, const drf_sched_config* sche
                                  const float* x_T, const void* cond, const void* null_cond, float cfg_scale,
                                  float* x_0_out, void* hip_stream)
 {
+    return drf_sample_noise(den, sched, mode, n, batch, x_T, cond, null_cond, cfg_scale, nullptr, x_0_out, hip_stream);
+}
+
+extern "C" drf_status drf_sample_noise(drf_denoiser* den, const drf_sched_config* sched, drf_mode mode, int n, int batch,
+                                       const float* x_T, const void* cond, const void* null_cond, float cfg_scale,
+                                       const drf_noise* noise, float* x_0_out, void* hip_stream)
+{
     if (!den) DRF_FAIL(DRF_EINVAL, "denoiser is NULL");
     Schedule sch;
     drf_status rc = make_schedule(sched, &sch);
@@ -546,6 +553,24 @@ extern "C" drf_status drf_sample(drf_denoiser* den, const drf_sched_config* sche
     if ((rc = build_plan(sch, mode, n, &passes, nullptr)) != DRF_OK) return rc;
     if (batch == 0) return DRF_OK;
     if (!x_T || !cond || !x_0_out) DRF_FAIL(DRF_EINVAL, "NULL buffer");
+    // coefficients (and the noise source) of every pass's update, checked before any launch
+    std::vector<UpdateArgs> updates(passes.size());
+    for (size_t k = 0; k < passes.size(); ++k) {
+        const Pass& p = passes[k];
+        UpdateArgs& u = updates[k];
+        u = UpdateArgs{};
+        u.n_chain = (int)p.chain.size();
+        for (int i = 0; i < u.n_chain; ++i) {
+            if ((rc = sch.coef(p.chain[(size_t)i].first, p.chain[(size_t)i].second, &u.cA[i], &u.cB[i], &u.cC[i])) != DRF_OK) return rc;
+            u.cz[i] = p.chain_z[(size_t)i];
+        }
+        u.n_draft = (int)p.draft_to.size();
+        for (int j = 0; j < u.n_draft; ++j) {
+            if ((rc = sch.coef(p.s_after, p.draft_to[(size_t)j], &u.dA[j], &u.dB[j], &u.dC[j])) != DRF_OK) return rc;
+            u.dz[j] = p.draft_z[(size_t)j];
+        }
+        if ((rc = set_noise_source(&u, noise)) != DRF_OK) return rc;
+    }
     hipStream_t st = (hipStream_t)hip_stream;
     const DitDims& dm = den->dm;
     const int g = null_cond ? 2 : 1, gB = g * batch;
@@ -600,7 +625,7 @@ extern "C" drf_status drf_sample(drf_denoiser* den, const drf_sched_config* sche
         };
         for (const Pass& p : passes)
             for (int s_eval : p.eval_s) {
-                map.taus[ng++] = sch.tau(s_eval);
+                map.taus[ng++] = sch.net_time(s_eval);
                 if (ng == kMaxBlock && (rc = flush()) != DRF_OK) return rc;
             }
         if ((rc = flush()) != DRF_OK) return rc;
@@ -608,23 +633,20 @@ extern "C" drf_status drf_sample(drf_denoiser* den, const drf_sched_config* sche
 
     const float* x_anchor = x_T;                    // state the next stand-alone pass evaluates
     size_t mod_row = 0;
-    for (const Pass& p : passes) {
+    for (size_t k = 0; k < passes.size(); ++k) {
+        const Pass& p = passes[k];
         const int groups = (int)p.eval_s.size();
         SlotMap map{};
         map.t_dev = nullptr; map.group = gB; map.x_group = gB; map.x_batch = batch; map.cond_mod = gB;
-        for (int i = 0; i < groups; ++i) map.taus[i] = sch.tau(p.eval_s[(size_t)i]);
+        for (int i = 0; i < groups; ++i) map.taus[i] = sch.net_time(p.eval_s[(size_t)i]);
         const float* xin = p.solo ? x_anchor : den->drafts;
         if ((rc = forward(den, xin, map, den->mod + mod_row * den->n_mod, groups * gB, dm.L, den->epsbuf, nullptr, st)) != DRF_OK) return rc;
         mod_row += (size_t)groups * gB;
 
-        UpdateArgs u{};
+        UpdateArgs& u = updates[k];
         u.x_base = p.base_is_draft ? den->drafts : x_anchor;
         u.eps = den->epsbuf; u.field = field; u.g = g; u.w = cfg_scale;
-        u.n_chain = (int)p.chain.size();
-        for (int i = 0; i < u.n_chain; ++i) sch.coef(p.chain[(size_t)i].first, p.chain[(size_t)i].second, &u.cA[i], &u.cB[i]);
         u.anchor_field = p.anchor_field < 0 ? 0 : p.anchor_field;
-        u.n_draft = (int)p.draft_to.size();
-        for (int j = 0; j < u.n_draft; ++j) sch.coef(p.s_after, p.draft_to[(size_t)j], &u.dA[j], &u.dB[j]);
         if (p.writes_x0) {
             if (u.n_draft > 0) { u.draft_out = x_0_out; u.x_out = nullptr; }      // the lone draft to index 0 is x_0
             else { u.x_out = x_0_out; u.draft_out = nullptr; }

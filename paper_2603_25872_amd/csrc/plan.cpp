@@ -26,7 +26,10 @@ drf_status make_schedule(const drf_sched_config* sc, Schedule* out)
         DRF_FAIL(DRF_EINVAL, "need 1 <= steps (%d) <= train_steps (%d), train_steps >= 2", sc->steps, sc->train_steps);
     if (!(sc->beta_start > 0.0) || !(sc->beta_end < 1.0) || !(sc->beta_start <= sc->beta_end))
         DRF_FAIL(DRF_EINVAL, "need 0 < beta_start <= beta_end < 1");
-    if (sc->eta != 0.0) DRF_FAIL(DRF_EUNSUPPORTED, "only eta = 0 (zero-variance DDIM skip transitions) is built");
+    if (sc->sampler != DRF_DDIM && sc->sampler != DRF_DDPM && sc->sampler != DRF_EULER)
+        DRF_FAIL(DRF_EINVAL, "unknown sampler %d", (int)sc->sampler);
+    if (sc->sampler == DRF_DDIM && !(sc->eta >= 0.0 && sc->eta <= 1.0)) DRF_FAIL(DRF_EINVAL, "need 0 <= eta <= 1");
+    if (sc->sampler == DRF_EULER && !(sc->shift > 0.0)) DRF_FAIL(DRF_EINVAL, "need shift > 0 for the Euler sigma grid");
     // The paper's alpha_t is cumulative (forward marginal x_t = sqrt(alpha_t) x_0 + sqrt(1 - alpha_t) eps).
     out->abar.resize((size_t)sc->train_steps);
     double run = 1.0;
@@ -37,17 +40,65 @@ drf_status make_schedule(const drf_sched_config* sc, Schedule* out)
     }
     out->steps = sc->steps;
     out->stride = sc->train_steps / sc->steps;
+    out->train_steps = sc->train_steps;
+    out->sampler = sc->sampler;
+    out->eta = sc->sampler == DRF_DDIM ? sc->eta : 0.0;
+    out->shift = sc->sampler == DRF_EULER ? sc->shift : 1.0;
     return DRF_OK;
 }
 
-// Eq. ddim_skip_reverse with sigma = 0, with the predicted x_0 substituted:
-//   x_to = sqrt(ab_to) (x - sqrt(1-ab_from) eps)/sqrt(ab_from) + sqrt(1-ab_to) eps = A x + B eps.
-void Schedule::coef(int s_from, int s_to, float* A, float* B) const
+// Discretisation of the ODE time (section "Euler ODE Solvers" leaves the grid open): uniform in
+// u = s / S from 0 (data) to 1 (noise), warped by sigma = shift u / (1 + (shift - 1) u).
+double Schedule::sigma_at(int s) const
 {
+    const double u = (double)s / (double)steps;
+    return shift * u / (1.0 + (shift - 1.0) * u);
+}
+
+int Schedule::net_time(int s) const
+{
+    if (sampler == DRF_EULER) return (int)std::floor(sigma_at(s) * (double)train_steps + 0.5);
+    return tau(s);
+}
+
+// Every skip transition is affine in (x, net output, fresh noise): x_to = A x + B net + C z.
+//   DDIM (Eq. ddim_skip_reverse), predicted x_0 substituted:
+//     x_to = sqrt(ab_to) (x - sqrt(1-ab_from) eps)/sqrt(ab_from) + sqrt(1-ab_to-sigma^2) eps + sigma z,
+//     sigma = eta * sqrt(posterior variance of the same jump);
+//   DDPM (Eq. ddpm_skip_reverse_detail): mu' = [sqrt(r)(1-ab_to) x + sqrt(ab_to)(1-r) x_0_hat]/(1-ab_from),
+//     r = ab_from/ab_to, plus sqrt((1-r)(1-ab_to)/(1-ab_from)) z;
+//   Euler: x_to = x + (sigma_to - sigma_from) v.
+drf_status Schedule::coef(int s_from, int s_to, float* A, float* B, float* C) const
+{
+    if (sampler == DRF_EULER) {
+        *A = 1.f;
+        *B = (float)(sigma_at(s_to) - sigma_at(s_from));
+        *C = 0.f;
+        return DRF_OK;
+    }
     const double af = abar_at(s_from), at = abar_at(s_to);
+    double sd = 0.0;
+    if (stochastic() && s_to != s_from && s_to != 0) {
+        if (s_from < 1 || s_to > s_from)
+            DRF_FAIL(DRF_EINVAL, "a transition with variance must move towards data from an index >= 1 (got %d -> %d)",
+                     s_from, s_to);
+        sd = std::sqrt((1.0 - af / at) * (1.0 - at) / (1.0 - af));
+    }
+    if (sampler == DRF_DDPM) {
+        if (s_from < 1) DRF_FAIL(DRF_EINVAL, "the DDPM posterior needs s_from >= 1 (got %d)", s_from);
+        const double r = af / at;
+        const double w0 = std::sqrt(at) * (1.0 - r) / (1.0 - af);        // weight of the predicted x_0
+        *A = (float)(std::sqrt(r) * (1.0 - at) / (1.0 - af) + w0 / std::sqrt(af));
+        *B = (float)(-w0 * std::sqrt(1.0 - af) / std::sqrt(af));
+        *C = (float)sd;
+        return DRF_OK;
+    }
+    const double sigma = eta * sd;
     const double a = std::sqrt(at / af);
     *A = (float)a;
-    *B = (float)(std::sqrt(1.0 - at) - a * std::sqrt(1.0 - af));
+    *B = (float)(std::sqrt(1.0 - at - sigma * sigma) - a * std::sqrt(1.0 - af));
+    *C = (float)sigma;
+    return DRF_OK;
 }
 
 // Division by an invariant (round-up method): for d not a power of two let s = ceil(log2 d)
@@ -71,16 +122,21 @@ void set_rows_per_slot(Epilogue* e, int d)
 namespace {
 struct RowSink {
     std::vector<int32_t>* rows;
-    void put(int round, int kind, int from, int to, int tau)
+    int draws = 0;              // kind-1 and kind-2 rows so far: each draws one fresh-noise field
+    // returns the ordinal of the row's draw (kind 1, 2), else -1
+    int put(int round, int kind, int from, int to, int tau)
     {
-        if (!rows) return;
-        const int32_t r[DRF_PLAN_ROW] = { round, kind, from, to, tau };
-        rows->insert(rows->end(), r, r + DRF_PLAN_ROW);
+        if (rows) {
+            const int32_t r[DRF_PLAN_ROW] = { round, kind, from, to, tau };
+            rows->insert(rows->end(), r, r + DRF_PLAN_ROW);
+        }
+        return kind == 0 ? -1 : draws++;
     }
 };
 }  // namespace
 
-drf_status build_plan(const Schedule& sch, drf_mode mode, int n, std::vector<Pass>* passes, std::vector<int32_t>* rows)
+drf_status build_plan(const Schedule& sch, drf_mode mode, int n, std::vector<Pass>* passes, std::vector<int32_t>* rows,
+                      size_t* n_noise)
 {
     if (n < 1) DRF_FAIL(DRF_EINVAL, "block size n must be >= 1 (got %d)", n);
     if (mode != DRF_CONSERVATIVE && mode != DRF_AGGRESSIVE) DRF_FAIL(DRF_EINVAL, "unknown mode %d", (int)mode);
@@ -92,9 +148,14 @@ drf_status build_plan(const Schedule& sch, drf_mode mode, int n, std::vector<Pas
 
     // Fills the `draft_to` of a pass whose update leaves an anchor pair at index s:
     // drafts to s-1 .. s-m.  A draft landing on 0 is only kept when it is x_0 itself (m == 1).
+    // The rows of these drafts are the next ones emitted, so draft i draws field sink.draws + i - 1
+    // (a draft that is not kept still has its row and its draw).
     auto plan_drafts = [&](Pass& p, int s, int m) {
         for (int i = 1; i <= m; ++i)
-            if (s - i >= 1 || i == 1) p.draft_to.push_back(s - i);
+            if (s - i >= 1 || i == 1) {
+                p.draft_to.push_back(s - i);
+                p.draft_z.push_back(sink.draws + i - 1);
+            }
         if (m == 1 && s == 1) p.writes_x0 = true;
     };
 
@@ -105,7 +166,7 @@ drf_status build_plan(const Schedule& sch, drf_mode mode, int n, std::vector<Pas
         Pass first;
         first.round = round; first.solo = true; first.s_anchor = s; first.eval_s = { s };
         first.anchor_field = 0; first.s_after = s;
-        sink.put(round, 0, s, s, sch.tau(s));
+        sink.put(round, 0, s, s, sch.net_time(s));
         int m = n < s ? n : s;
         plan_drafts(first, s, m);
         P.push_back(first);
@@ -114,13 +175,15 @@ drf_status build_plan(const Schedule& sch, drf_mode mode, int n, std::vector<Pas
             m = n < s ? n : s;
             const bool evaluates = s >= 2;          // a block whose only draft is x_0 runs no pass
             const int r = evaluates ? round : round - 1;
-            for (int i = 1; i <= m; ++i) sink.put(r, 1, s, s - i, s - i >= 1 ? sch.tau(s - i) : -1);
-            for (int i = 2; i <= m; ++i) sink.put(r, 2, s - i + 1, s - i, -1);
+            for (int i = 1; i <= m; ++i) sink.put(r, 1, s, s - i, s - i >= 1 ? sch.net_time(s - i) : -1);
+            std::vector<int> zs;
+            for (int i = 2; i <= m; ++i) zs.push_back(sink.put(r, 2, s - i + 1, s - i, -1));
             if (!evaluates) break;                  // x_0 was written by the previous pass's update
             Pass p;
             p.round = round; p.s_anchor = s; p.base_is_draft = true;
             for (int i = 1; i <= m && s - i >= 1; ++i) p.eval_s.push_back(s - i);
             for (int i = 2; i <= m; ++i) p.chain.push_back({ s - i + 1, s - i });
+            p.chain_z = zs;
             s -= m;
             p.s_after = s;
             if (s > 0) {
@@ -139,27 +202,30 @@ drf_status build_plan(const Schedule& sch, drf_mode mode, int n, std::vector<Pas
             Pass solo;
             solo.round = round; solo.solo = true; solo.s_anchor = s; solo.eval_s = { s };
             solo.anchor_field = 0; solo.s_after = s;
-            sink.put(round, 0, s, s, sch.tau(s));
+            sink.put(round, 0, s, s, sch.net_time(s));
             const int m = n < s - 1 ? n : s - 1;
             if (m == 0) {                           // a single step is left: plain update 1 -> 0
-                sink.put(round, 2, s, s - 1, -1);
+                solo.draft_z = { sink.put(round, 2, s, s - 1, -1) };
                 solo.draft_to = { 0 };
                 solo.writes_x0 = true;
                 P.push_back(solo);
                 break;
             }
-            for (int i = 1; i <= m; ++i) solo.draft_to.push_back(s - i);
+            for (int i = 1; i <= m; ++i) {
+                solo.draft_to.push_back(s - i);
+                solo.draft_z.push_back(sink.draws + i - 1);     // the kind-1 rows below
+            }
             P.push_back(solo);
             ++round;
             Pass p;
             p.round = round; p.s_anchor = s; p.base_is_draft = true;
             for (int i = 1; i <= m; ++i) {
                 p.eval_s.push_back(s - i);
-                sink.put(round, 1, s, s - i, sch.tau(s - i));
+                sink.put(round, 1, s, s - i, sch.net_time(s - i));
             }
             for (int i = 2; i <= m + 1; ++i) {
                 p.chain.push_back({ s - i + 1, s - i });
-                sink.put(round, 2, s - i + 1, s - i, -1);
+                p.chain_z.push_back(sink.put(round, 2, s - i + 1, s - i, -1));
             }
             s -= m + 1;
             p.s_after = s;
@@ -168,6 +234,20 @@ drf_status build_plan(const Schedule& sch, drf_mode mode, int n, std::vector<Pas
             ++round;
         }
     }
+    if (n_noise) *n_noise = (size_t)sink.draws;
+    return DRF_OK;
+}
+
+drf_status set_noise_source(UpdateArgs* a, const drf_noise* noise)
+{
+    bool needed = false;
+    for (int i = 0; i < a->n_chain; ++i) needed = needed || a->cC[i] != 0.f;
+    for (int j = 0; j < a->n_draft; ++j) needed = needed || a->dC[j] != 0.f;
+    a->noise_mode = NOISE_NONE; a->z = nullptr; a->seed = 0; a->z_field0 = 0;
+    if (!needed) return DRF_OK;
+    if (!noise) DRF_FAIL(DRF_EINVAL, "this sampler adds fresh noise: a noise source is required");
+    if (noise->z) { a->noise_mode = NOISE_EXPLICIT; a->z = noise->z; }
+    else { a->noise_mode = NOISE_PHILOX; a->seed = noise->seed; a->z_field0 = noise->field0; }
     return DRF_OK;
 }
 
@@ -191,4 +271,13 @@ extern "C" drf_status drf_plan_build(const drf_sched_config* sched, drf_mode mod
         for (size_t i = 0; i < take; ++i) rows[i] = table[i];
     }
     return DRF_OK;
+}
+
+extern "C" drf_status drf_noise_count(const drf_sched_config* sched, drf_mode mode, int n, size_t* count)
+{
+    drf::Schedule sch;
+    drf_status st = drf::make_schedule(sched, &sch);
+    if (st != DRF_OK) return st;
+    if (!count) DRF_FAIL(DRF_EINVAL, "count is NULL");
+    return drf::build_plan(sch, mode, n, nullptr, nullptr, count);
 }

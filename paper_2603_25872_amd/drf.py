@@ -16,9 +16,11 @@ F32, BF16 = 0, 1
 COND_VECTOR, COND_CLASS, COND_TEXT = 0, 1, 2
 PLAN_ROW = 5
 PROF_GEMM, PROF_ATTN, PROF_ELEMWISE, PROF_UPDATE = 0, 1, 2, 3
+DDIM, DDPM, EULER = 0, 1, 2
 
 SYMBOLS = ["drf_denoiser_weight_count", "drf_denoiser_create", "drf_denoiser_destroy", "drf_denoiser_reserve",
            "drf_eps_batched", "drf_eps_trace", "drf_skip_transition", "drf_refine_step", "drf_sample",
+           "drf_skip_transition_noise", "drf_normal_fill", "drf_sample_noise", "drf_noise_count",
            "drf_plan_build", "drf_profile_enable", "drf_profile_read", "drf_probe_gemm_bf16", "drf_probe_attn_bf16", "drf_last_error"]
 
 
@@ -29,7 +31,11 @@ class DitConfig(C.Structure):
 
 class SchedConfig(C.Structure):
     _fields_ = [("train_steps", C.c_int), ("beta_start", C.c_double), ("beta_end", C.c_double),
-                ("steps", C.c_int), ("eta", C.c_double)]
+                ("steps", C.c_int), ("eta", C.c_double), ("sampler", C.c_int), ("shift", C.c_double)]
+
+
+class Noise(C.Structure):
+    _fields_ = [("z", C.c_void_p), ("seed", C.c_uint64), ("field0", C.c_uint32)]
 
 
 class DrfError(RuntimeError):
@@ -64,6 +70,12 @@ def lib():
         L.drf_sample.argtypes = [C.c_void_p, C.c_void_p, C.c_int, C.c_int, C.c_int, C.c_void_p, C.c_void_p,
                                  C.c_void_p, C.c_float, C.c_void_p, C.c_void_p]
         L.drf_plan_build.argtypes = [C.c_void_p, C.c_int, C.c_int, C.c_void_p, C.c_size_t, C.c_void_p]
+        L.drf_skip_transition_noise.argtypes = [C.c_void_p, C.c_void_p, C.c_void_p, C.c_int, C.c_void_p, C.c_int, C.c_int,
+                                                C.c_size_t, C.c_void_p, C.c_void_p, C.c_void_p]
+        L.drf_normal_fill.argtypes = [C.c_uint64, C.c_uint32, C.c_size_t, C.c_size_t, C.c_void_p, C.c_void_p]
+        L.drf_sample_noise.argtypes = [C.c_void_p, C.c_void_p, C.c_int, C.c_int, C.c_int, C.c_void_p, C.c_void_p,
+                                       C.c_void_p, C.c_float, C.c_void_p, C.c_void_p, C.c_void_p]
+        L.drf_noise_count.argtypes = [C.c_void_p, C.c_int, C.c_int, C.c_void_p]
         L.drf_profile_enable.argtypes = [C.c_void_p, C.c_int]
         L.drf_profile_read.argtypes = [C.c_void_p, C.c_int, C.c_void_p, C.c_void_p, C.c_void_p]
         L.drf_probe_gemm_bf16.argtypes = [C.c_void_p, C.c_void_p, C.c_int, C.c_int, C.c_int, C.c_void_p, C.c_void_p,
@@ -85,7 +97,18 @@ def dit_config(d):
 
 
 def sched_config(d):
-    return SchedConfig(d["train_steps"], d["beta_start"], d["beta_end"], d["steps"], d.get("eta", 0.0))
+    return SchedConfig(d["train_steps"], d["beta_start"], d["beta_end"], d["steps"], float(d.get("eta", 0.0)),
+                       int(d.get("sampler", DDIM)), float(d.get("shift", 1.0)))
+
+
+def _noise(z=None, seed=None, field0=0):
+    """drf_noise from explicit device fields z, or (seed, field0) of the library's stream; None when neither is given."""
+    import torch
+    if z is not None:
+        return Noise(_dev(z, torch.float32), 0, 0)
+    if seed is not None:
+        return Noise(None, int(seed), int(field0))
+    return None
 
 
 def _stream():
@@ -132,6 +155,41 @@ def skip_transition(sched, x_from, eps_from, s_from, s_to, out=None):
     _check(lib().drf_skip_transition(C.byref(sc), _dev(x_from, torch.float32), _dev(eps_from, torch.float32), s_from,
                                      tgt, m, batch, elems, _dev(out, torch.float32), _stream()))
     return out
+
+
+def skip_transition_noise(sched, x_from, net_from, s_from, s_to, z=None, seed=None, field0=0, out=None):
+    """Skip transitions of the configured sampler with their fresh noise: explicit fields z [len(s_to), batch, ...]
+    or the library's stream (seed, field0)."""
+    import torch
+    sc = sched_config(sched)
+    m = len(s_to)
+    batch = x_from.shape[0] if x_from.dim() > 0 else 1
+    elems = x_from.numel() // batch if batch else 0
+    if out is None:
+        out = torch.empty((m,) + tuple(x_from.shape), dtype=torch.float32, device=x_from.device)
+    tgt = (C.c_int * max(m, 1))(*s_to)
+    nz = _noise(z, seed, field0)
+    _check(lib().drf_skip_transition_noise(C.byref(sc), _dev(x_from, torch.float32), _dev(net_from, torch.float32),
+                                           s_from, tgt, m, batch, elems, C.byref(nz) if nz is not None else None,
+                                           _dev(out, torch.float32), _stream()))
+    return out
+
+
+def normal_fill(seed, field0, n_fields, field_elems, out=None):
+    """Fields field0 .. field0 + n_fields - 1 of the library's normal stream as a device tensor [n_fields, field_elems]."""
+    import torch
+    if out is None:
+        out = torch.empty((n_fields, field_elems), dtype=torch.float32, device="cuda")
+    _check(lib().drf_normal_fill(int(seed), int(field0), n_fields, field_elems, _dev(out, torch.float32), _stream()))
+    return out
+
+
+def noise_count(sched, mode, n):
+    """Number of fresh-noise fields one drf_sample_noise call draws (host only)."""
+    sc = sched_config(sched)
+    cnt = C.c_size_t(0)
+    _check(lib().drf_noise_count(C.byref(sc), mode, n, C.byref(cnt)))
+    return int(cnt.value)
 
 
 def refine_step(sched, x, eps, s_from, out=None):
@@ -217,6 +275,19 @@ class Denoiser:
         _check(lib().drf_sample(self.h, C.byref(sc), mode, n, x_T.shape[0], _dev(x_T, torch.float32),
                                 _dev(cond, self._cond_dtype()), _dev(null_cond, self._cond_dtype()),
                                 float(cfg_scale or 0.0), _dev(out, torch.float32), _stream()))
+        return out
+
+    def sample_noise(self, sched, mode, n, x_T, cond, null_cond=None, cfg_scale=0.0, z=None, seed=None, field0=0,
+                     out=None):
+        import torch
+        sc = sched_config(sched)
+        if out is None:
+            out = torch.empty_like(x_T)
+        nz = _noise(z, seed, field0)
+        _check(lib().drf_sample_noise(self.h, C.byref(sc), mode, n, x_T.shape[0], _dev(x_T, torch.float32),
+                                      _dev(cond, self._cond_dtype()), _dev(null_cond, self._cond_dtype()),
+                                      float(cfg_scale or 0.0), C.byref(nz) if nz is not None else None,
+                                      _dev(out, torch.float32), _stream()))
         return out
 
     def profile_enable(self, on=True):

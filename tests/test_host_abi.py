@@ -56,16 +56,61 @@ def test_plan_capacity_is_respected():
     assert (rows[2] == -7).all() and (rows[:2] != -7).any()
 
 
-@pytest.mark.parametrize("bad", [dict(steps=0), dict(steps=1001), dict(eta=0.5), dict(beta_start=0.0),
-                                 dict(beta_end=1.0), dict(train_steps=1)])
+@pytest.mark.parametrize("bad", [dict(steps=0), dict(steps=1001), dict(eta=1.5), dict(eta=-0.1), dict(beta_start=0.0),
+                                 dict(beta_end=1.0), dict(train_steps=1), dict(sampler=3), dict(sampler=-1),
+                                 dict(sampler=drf.EULER, shift=0.0)])
 def test_bad_schedule_is_a_status_code(bad):
     sc = drf.sched_config(dict(sched(20), **bad))
     cnt = C.c_size_t(0)
     st = drf.lib().drf_plan_build(C.byref(sc), 0, 2, None, 0, C.byref(cnt))
-    assert st in (-1, -5)
+    assert st == -1
     assert len(drf.lib().drf_last_error()) > 0
-    if "eta" in bad:
-        assert st == -5
+
+
+@pytest.mark.parametrize("mode", [drf.CONSERVATIVE, drf.AGGRESSIVE])
+@pytest.mark.parametrize("S", [1, 2, 3, 7, 28, 50])
+@pytest.mark.parametrize("n", [1, 2, 4, 9])
+@pytest.mark.parametrize("extra", [dict(eta=1.0), dict(sampler=drf.DDPM), dict(sampler=drf.EULER),
+                                   dict(sampler=drf.EULER, shift=3.0)])
+def test_plan_and_draw_count_of_the_other_samplers(orc, mode, S, n, extra):
+    sd = dict(sched(S), **extra)
+    got = drf.plan_build(sd, mode, n)
+    assert np.array_equal(got, orc.plan(sd, mode, n))
+    assert drf.noise_count(sd, mode, n) == orc.noise_count(sd, mode, n) == int((got[:, 1] != 0).sum())
+
+
+def test_euler_plan_feeds_sigma_scaled_times(orc):
+    sd = dict(sched(28), sampler=drf.EULER, shift=3.0)
+    rows = drf.plan_build(sd, drf.CONSERVATIVE, 4)
+    evald = rows[rows[:, 4] >= 0]
+    for r in evald:
+        u = r[3] / 28
+        assert r[4] == int(np.floor(3 * u / (1 + 2 * u) * 1000 + 0.5))
+    assert evald[0, 4] == 1000
+
+
+def test_stochastic_sampler_without_noise_source_is_rejected_before_any_launch():
+    # validation happens on the host: fake (never dereferenced) device addresses are enough
+    L = drf.lib()
+    fake = C.c_void_p(0x1000)
+    to = (C.c_int * 2)(4, 3)
+    for extra in (dict(eta=0.5), dict(sampler=drf.DDPM)):
+        sc = drf.sched_config(dict(sched(20), **extra))
+        assert L.drf_skip_transition_noise(C.byref(sc), fake, fake, 5, to, 2, 1, 16, None, fake, None) == -1
+        assert b"noise source" in L.drf_last_error()
+        assert L.drf_skip_transition(C.byref(sc), fake, fake, 5, to, 2, 1, 16, fake, None) == -1
+        # a transition with variance has to move towards data
+        up = (C.c_int * 1)(7)
+        nz = drf.Noise(None, 1, 0)
+        assert L.drf_skip_transition_noise(C.byref(sc), fake, fake, 5, up, 1, 1, 16, C.byref(nz), fake, None) == -1
+        assert b"towards data" in L.drf_last_error()
+    cnt = C.c_size_t(0)
+    sc = drf.sched_config(sched(20))
+    assert L.drf_noise_count(C.byref(sc), 0, 2, None) == -1
+    assert L.drf_noise_count(C.byref(sc), 0, 0, C.byref(cnt)) == -1
+    assert L.drf_normal_fill(1, 0, 4, 16, None, None) == -1
+    assert L.drf_normal_fill(1, 0, 0, 16, None, None) == 0
+    assert L.drf_normal_fill(1, 0xffffffff, 2, 16, fake, None) == -1
 
 
 def test_bad_plan_arguments():

@@ -367,7 +367,7 @@ def test_normal_fill_layout(orc):
     assert len(np.unique(a)) == a.size
     # element 4q+j comes from block q word pair: Box-Muller written out
     r = orc.philox([5, 0, 2, 0], [99, 0])
-    u = [((w >> 8) + 0.5) / 2 ** 24 for w in r]
+    u = [((w >> 9) + 0.5) / 2 ** 23 for w in r]
     want = [math.sqrt(-2 * math.log(u[0])) * math.cos(2 * math.pi * u[1]),
             math.sqrt(-2 * math.log(u[0])) * math.sin(2 * math.pi * u[1]),
             math.sqrt(-2 * math.log(u[2])) * math.cos(2 * math.pi * u[3]),
@@ -376,7 +376,7 @@ def test_normal_fill_layout(orc):
     # the seed's high word is the second key word
     b = orc.normal_fill((7 << 32) | 99, 0, 1, 8)
     r = orc.philox([0, 0, 0, 0], [99, 7])
-    u0, u1 = ((r[0] >> 8) + 0.5) / 2 ** 24, ((r[1] >> 8) + 0.5) / 2 ** 24
+    u0, u1 = ((r[0] >> 9) + 0.5) / 2 ** 23, ((r[1] >> 9) + 0.5) / 2 ** 23
     assert abs(b[0, 0] - math.sqrt(-2 * math.log(u0)) * math.cos(2 * math.pi * u1)) < 1e-12
 
 
