@@ -46,6 +46,11 @@ def main():
     ap.add_argument("--config", type=int, default=3, help="workload configuration 1..5")
     ap.add_argument("--n", type=int, default=None, help="override the block size n")
     ap.add_argument("--mode", type=int, default=None, help="0 conservative, 1 aggressive")
+    ap.add_argument("--batch", type=int, default=None, help="override the batch size")
+    ap.add_argument("--sampler", type=int, default=0, help="0 DDIM, 1 DDPM posterior, 2 Euler (velocity net)")
+    ap.add_argument("--eta", type=float, default=0.0, help="DDIM: variance scale of the skip transitions")
+    ap.add_argument("--shift", type=float, default=1.0, help="Euler: time shift of the sigma grid")
+    ap.add_argument("--seed", type=int, default=1, help="seed of the library's noise stream (stochastic samplers)")
     ap.add_argument("--no-cpu-baseline", action="store_true")
     ap.add_argument("--no-roofline", action="store_true")
     args = ap.parse_args()
@@ -58,10 +63,13 @@ def main():
     from paper_2603_25872_amd import drf, inputs as I
 
     cfg = I.config(args.config)
-    dit, sd = cfg["dit"], cfg["sched"]
+    dit, sd = cfg["dit"], dict(cfg["sched"], sampler=args.sampler, eta=args.eta, shift=args.shift)
     n = cfg["n"] if args.n is None else args.n
     mode = cfg["mode"] if args.mode is None else args.mode
-    B, S = cfg["batch"], sd["steps"]
+    B, S = (cfg["batch"] if args.batch is None else args.batch), sd["steps"]
+    stochastic = args.sampler == 1 or (args.sampler == 0 and args.eta != 0.0)
+    default_workload = (args.n is None and args.mode is None and args.batch is None and args.sampler == 0
+                        and args.eta == 0.0)
     g = 2 if cfg["guidance"] else 1
     assert torch.cuda.is_available(), "bench.py needs a GPU"
 
@@ -74,7 +82,10 @@ def main():
     out = torch.empty_like(xT)
 
     def step():
-        den.sample(sd, mode, n, xT, cond, null, cfg["guidance"] or 0.0, out=out)
+        if stochastic:      # fresh noise generated inside the update kernel from the library's stream
+            den.sample_noise(sd, mode, n, xT, cond, null, cfg["guidance"] or 0.0, seed=args.seed, out=out)
+        else:
+            den.sample(sd, mode, n, xT, cond, null, cfg["guidance"] or 0.0, out=out)
 
     for _ in range(args.warmup):
         step()
@@ -99,8 +110,10 @@ def main():
         "higher_is_better": True, "scaling": "weak", "vs_baseline": None,
         "dtype": "bf16" if dit["dtype"] == I.BF16 else "f32",
         "data": "synthetic",
-        "config": {"workload": "config %d: %s, %d-step DDIM, %s n=%d, batch %d, guidance %s" % (
-            args.config, cfg["name"], S, "aggressive" if mode else "conservative", n, B, cfg["guidance"]),
+        "config": {"workload": "config %d: %s, %d-step %s, %s n=%d, batch %d, guidance %s" % (
+            args.config, cfg["name"], S,
+            ["DDIM eta=%g" % args.eta if args.eta else "DDIM", "DDPM skip", "Euler shift=%g" % args.shift][args.sampler],
+            "aggressive" if mode else "conservative", n, B, cfg["guidance"]),
             "slots_per_full_pass": n * g * B, "evals_per_step": evals},
         "achieved_tflops_whole_call": flops_call / (ms_step * 1e-3) / 1e12,
         "frac_of_bf16_mfma_peak_whole_call": flops_call / (ms_step * 1e-3) / 1e12 / PEAK_BF16_TFLOPS,
@@ -118,7 +131,7 @@ def main():
         result["roofline"] = {"bound": "mfma", "kernel": "gemm_bf16_xl_kernel (all bf16 GEMM launches of one drf_sample call)",
                               "achieved": ach, "peak": PEAK_BF16_TFLOPS, "unit": "TFLOP/s",
                               "frac": ach / PEAK_BF16_TFLOPS,
-                              "traffic": GEMM_TRAFFIC_BYTES_PER_LAUNCH.get(args.config) if args.n is None and args.mode is None else None,
+                              "traffic": GEMM_TRAFFIC_BYTES_PER_LAUNCH.get(args.config) if default_workload else None,
                               "launches": gm["launches"], "avg_launch_us": gm["ms"] * 1e3 / max(gm["launches"], 1),
                               "flops_per_launch": gm["work"] / max(gm["launches"], 1)}
         result["families_ms"] = {k: round(v["ms"], 3) for k, v in fam.items()}
@@ -137,16 +150,29 @@ def main():
         eb = torch.randn((big, E), device="cuda")
         ob = torch.empty((4, big, E), device="cuda")
         targets = [S - 1, S - 2, S - 3, S - 4] if S >= 5 else [0] * 4
-        drf.skip_transition(sd, xb, eb, S, targets, out=ob)
+        sd0 = cfg["sched"]
+        drf.skip_transition(sd0, xb, eb, S, targets, out=ob)
         e0, e1 = torch.cuda.Event(enable_timing=True), torch.cuda.Event(enable_timing=True)
         e0.record()
         for _ in range(10):
-            drf.skip_transition(sd, xb, eb, S, targets, out=ob)
+            drf.skip_transition(sd0, xb, eb, S, targets, out=ob)
         e1.record()
         torch.cuda.synchronize()
         us = e0.elapsed_time(e1) * 100.0
         result["update_kernel_scaled"] = {"batch": big, "bytes_per_launch": 6 * big * E * 4, "us_per_launch": us,
                                           "achieved_GBps": 6 * big * E * 4 / (us * 1e-6) / 1e9, "peak_GBps": PEAK_HBM_GBS}
+        # the same launch with variance: each of the 4 drafts adds its own generated normal field (no extra bytes)
+        sdn = dict(cfg["sched"], eta=1.0)
+        drf.skip_transition_noise(sdn, xb, eb, S, targets, seed=args.seed, out=ob)
+        e0.record()
+        for _ in range(10):
+            drf.skip_transition_noise(sdn, xb, eb, S, targets, seed=args.seed, out=ob)
+        e1.record()
+        torch.cuda.synchronize()
+        us = e0.elapsed_time(e1) * 100.0
+        result["update_kernel_scaled_noise"] = {"batch": big, "bytes_per_launch": 6 * big * E * 4, "us_per_launch": us,
+                                                "achieved_GBps": 6 * big * E * 4 / (us * 1e-6) / 1e9,
+                                                "normals_per_s": 4 * big * E / (us * 1e-6)}
         del xb, eb, ob
     den.close()
 

@@ -88,7 +88,7 @@ template <> __device__ inline float load_fresh<float>(const UpdateArgs& a, int o
     return comp(normal_block(a.seed, a.z_field0 + (uint32_t)ordinal, i >> 2), (int)(i & 3));
 }
 
-template <typename V>
+template <typename V, bool NOISE>
 __global__ void __launch_bounds__(256) update_kernel(const UpdateArgs a, size_t nvec)
 {
     const size_t stride = (size_t)gridDim.x * blockDim.x;
@@ -99,7 +99,7 @@ __global__ void __launch_bounds__(256) update_kernel(const UpdateArgs a, size_t 
             V e = load_noise<V>(a, c, i, nvec);
 #pragma unroll
             for (int k = 0; k < VecTraits<V>::N; ++k) setc(y, k, fmaf(a.cA[c], comp(y, k), a.cB[c] * comp(e, k)));
-            if (a.noise_mode != NOISE_NONE && a.cC[c] != 0.f) {
+            if (NOISE && a.cC[c] != 0.f) {
                 V z = load_fresh<V>(a, a.cz[c], i, nvec);
 #pragma unroll
                 for (int k = 0; k < VecTraits<V>::N; ++k) setc(y, k, fmaf(a.cC[c], comp(z, k), comp(y, k)));
@@ -113,7 +113,7 @@ __global__ void __launch_bounds__(256) update_kernel(const UpdateArgs a, size_t 
                 V d;
 #pragma unroll
                 for (int k = 0; k < VecTraits<V>::N; ++k) setc(d, k, fmaf(a.dA[j], comp(y, k), a.dB[j] * comp(e, k)));
-                if (a.noise_mode != NOISE_NONE && a.dC[j] != 0.f) {
+                if (NOISE && a.dC[j] != 0.f) {
                     V z = load_fresh<V>(a, a.dz[j], i, nvec);
 #pragma unroll
                     for (int k = 0; k < VecTraits<V>::N; ++k) setc(d, k, fmaf(a.dC[j], comp(z, k), comp(d, k)));
@@ -153,10 +153,15 @@ drf_status launch_update(const UpdateArgs& a, hipStream_t st)
     const size_t nvec = vec ? a.field / 4 : a.field;
     size_t blocks = (nvec + 255) / 256;
     if (blocks > 256 * 32) blocks = 256 * 32;      // grid-stride beyond 32 blocks per CU
-    if (vec)
-        hipLaunchKernelGGL(update_kernel<float4>, dim3((unsigned)blocks), dim3(256), 0, st, a, nvec);
+    const bool noise = a.noise_mode != NOISE_NONE;
+    if (vec && noise)
+        hipLaunchKernelGGL((update_kernel<float4, true>), dim3((unsigned)blocks), dim3(256), 0, st, a, nvec);
+    else if (vec)
+        hipLaunchKernelGGL((update_kernel<float4, false>), dim3((unsigned)blocks), dim3(256), 0, st, a, nvec);
+    else if (noise)
+        hipLaunchKernelGGL((update_kernel<float, true>), dim3((unsigned)blocks), dim3(256), 0, st, a, nvec);
     else
-        hipLaunchKernelGGL(update_kernel<float>, dim3((unsigned)blocks), dim3(256), 0, st, a, nvec);
+        hipLaunchKernelGGL((update_kernel<float, false>), dim3((unsigned)blocks), dim3(256), 0, st, a, nvec);
     DRF_HIP(hipGetLastError());
     return DRF_OK;
 }
