@@ -166,6 +166,30 @@ gemm_bf16_kernel(const bf16_t* __restrict__ A, const bf16_t* __restrict__ W, int
 #define DRF_GLOBAL_AS __attribute__((address_space(1)))
 #define DRF_LDS_AS __attribute__((address_space(3)))
 template <int N> __device__ inline void wait_vmcnt() { asm volatile("s_waitcnt vmcnt(%0)" ::"n"(N) : "memory"); }
+template <int N> __device__ inline void wait_lgkmcnt() { asm volatile("s_waitcnt lgkmcnt(%0)" ::"n"(N) : "memory"); }
+typedef uint32_t u32x4 __attribute__((ext_vector_type(4)));
+// 16 bytes per lane from LDS byte address addr + OFF, asynchronously: dst is valid only after an
+// s_waitcnt lgkmcnt that covers it.
+template <int OFF> __device__ inline void lds_read16(u32x4& dst, uint32_t addr)
+{
+    asm volatile("ds_read_b128 %0, %1 offset:%2" : "=v"(dst) : "v"(addr), "n"(OFF));
+}
+// Waits until at most N LDS reads are outstanding.  The fragments that the following MFMAs consume
+// pass through the statement as in/out operands, so no use of them can be scheduled above the wait.
+template <int N> __device__ inline void wait_frag(u32x4& w) { asm volatile("s_waitcnt lgkmcnt(%1)" : "+v"(w) : "n"(N)); }
+template <int N, int MI> __device__ inline void wait_frags(u32x4& w, u32x4 (&a)[MI])
+{
+    static_assert(MI == 2 || MI == 4, "activation fragments per k-step");
+    if constexpr (MI == 2) asm volatile("s_waitcnt lgkmcnt(%3)" : "+v"(w), "+v"(a[0]), "+v"(a[1]) : "n"(N));
+    else asm volatile("s_waitcnt lgkmcnt(%5)" : "+v"(w), "+v"(a[0]), "+v"(a[1]), "+v"(a[2]), "+v"(a[3]) : "n"(N));
+}
+template <int I, int N, typename F> __device__ __forceinline__ void static_for(F&& f)
+{
+    if constexpr (I < N) {
+        f(std::integral_constant<int, I>{});
+        static_for<I + 1, N>(f);
+    }
+}
 
 // ------------------------------------------------ bf16 MFMA 16x16x32, wide tiles
 // The main kernel for the DiT's big GEMMs.  BM x BN x 64 block tile (256 x 288 for hidden
@@ -254,34 +278,81 @@ gemm_bf16_xl_kernel(const bf16_t* __restrict__ A, const bf16_t* __restrict__ W, 
 #pragma unroll
     for (int ks = 0; ks < KS; ++ks) koff[ks] = l16 * BK + (((ks * 4 + quarter) ^ ((l16 / RB) & (CPR - 1))) << 3);
 
+    // Main loop, software-pipelined at the granularity of one weight fragment.  The MFMAs of a k-tile
+    // are G = KS * NI groups (one 16-column weight fragment against the MI activation fragments); the
+    // LDS read of the fragment for group g + D is issued just before the MFMAs of group g, into a ring
+    // of R = D + 1 register sets, and the activation fragments of a k-step are double-buffered the
+    // same way.  The block barrier that hands over the next k-tile (its DMA has landed, every wave has
+    // finished reading the current one) sits D groups before the end of the current tile, so each wave
+    // leaves it with D groups of MFMAs whose operands are already in registers while the first reads
+    // of the new tile are in flight: no LDS latency is exposed at the tile boundary.
+    // The fragment reads and their waits are written by hand (ds_read_b128 / s_waitcnt lgkmcnt(n)):
+    // with LDS-DMA in the loop the compiler's own wait insertion falls back to lgkmcnt(0), which
+    // exposes a full LDS round trip several times per tile.  LDS reads return in order, so before the
+    // MFMAs of group g it is enough that at most the reads issued after position g's remain.
+    static_assert(NS == 2 && KS == 2, "the pipelined loop assumes two LDS stages of two k-steps");
+    constexpr int G = KS * NI;
+    constexpr int R = G % 6 == 0 ? 6 : G % 4 == 0 ? 4 : G % 5 == 0 ? 5 : G % 3 == 0 ? 3 : 2, D = R - 1;
+    static_assert(G % R == 0 && D < NI && D + MI <= 15, "ring size");
     const int nk = K / (BK * WK);
+    u32x4 fa[2][MI], fw[R];
+    const uint32_t lds0 = (uint32_t)(uintptr_t)(DRF_LDS_AS unsigned char*)smem_raw;
+    uint32_t a_addr[KS], w_addr[KS];                // byte addresses of this lane's fragments in stage 0
 #pragma unroll
-    for (int s = 0; s < NS - 1; ++s)
-        if (s < nk) issue(s, s);
-    for (int kt = 0; kt < nk; ++kt) {
-        const int stage = kt % NS;
-        // tile kt has landed once only the NS-2 younger tiles remain in flight
-        if (kt + NS - 2 < nk) wait_vmcnt<LPT * (NS - 2)>(); else wait_vmcnt<0>();
-        __syncthreads();                     // ... for every wave, and all are done reading tile kt-1's stage
-        if (kt + NS - 1 < nk) issue(kt + NS - 1, (kt + NS - 1) % NS);
-        const bf16_t* pa = smem + stage * STAGE + wk * STAGE1 + wm * TM * BK;
-        const bf16_t* pw = smem + stage * STAGE + wk * STAGE1 + BM * BK + wn * TN * BK;
-#pragma unroll
-        for (int ks = 0; ks < KS; ++ks) {
-            bf16x8 fa[MI], fw[NI];
-#pragma unroll
-            for (int j = 0; j < MI; ++j) fa[j] = *reinterpret_cast<const bf16x8*>(pa + j * 16 * BK + koff[ks]);
-#pragma unroll
-            for (int i = 0; i < NI; ++i) fw[i] = *reinterpret_cast<const bf16x8*>(pw + i * 16 * BK + koff[ks]);
-            __builtin_amdgcn_s_setprio(1);
-#pragma unroll
-            for (int i = 0; i < NI; ++i)
-#pragma unroll
-                for (int j = 0; j < MI; ++j)
-                    acc[i][j] = __builtin_amdgcn_mfma_f32_16x16x32_bf16(fw[i], fa[j], acc[i][j], 0, 0, 0);
-            __builtin_amdgcn_s_setprio(0);
-        }
+    for (int ks = 0; ks < KS; ++ks) {
+        a_addr[ks] = lds0 + (uint32_t)(wk * STAGE1 + wm * TM * BK + koff[ks]) * 2u;
+        w_addr[ks] = lds0 + (uint32_t)(wk * STAGE1 + BM * BK + wn * TN * BK + koff[ks]) * 2u;
     }
+    // reads of stream position p (0 <= p < G) of a k-tile; aa / wa: this lane's fragment addresses in its stage
+    auto fetch = [&](auto pc, const uint32_t (&aa)[KS], const uint32_t (&wa)[KS]) {
+        constexpr int p = decltype(pc)::value, ks = p / NI, i = p % NI;
+        if constexpr (i == 0)
+            static_for<0, MI>([&](auto jc) {
+                constexpr int j = decltype(jc)::value;
+                lds_read16<j * 16 * BK * 2>(fa[ks & 1][j], aa[ks]);
+            });
+        lds_read16<i * 16 * BK * 2>(fw[p % R], wa[ks]);
+    };
+
+    issue(0, 0);
+    asm volatile("s_waitcnt vmcnt(0)\n\ts_barrier" ::: "memory");
+    if (1 < nk) issue(1, 1);
+    static_for<0, D>([&](auto pc) { fetch(pc, a_addr, w_addr); });
+    for (int kt = 0; kt < nk; ++kt) {
+        const uint32_t co = (uint32_t)(kt & 1) * (uint32_t)(STAGE * 2), no = (uint32_t)(STAGE * 2) - co;
+        uint32_t ca[KS], cw[KS], na[KS], nw[KS];
+#pragma unroll
+        for (int ks = 0; ks < KS; ++ks) { ca[ks] = a_addr[ks] + co; cw[ks] = w_addr[ks] + co; na[ks] = a_addr[ks] + no; nw[ks] = w_addr[ks] + no; }
+        static_for<0, G>([&](auto gc) {
+            constexpr int g = decltype(gc)::value;
+            if constexpr (g + D == G) {
+                // tile kt+1 has landed (vmcnt 0) and this wave's reads of tile kt are complete (lgkmcnt 0), for
+                // every wave after the barrier: the stage of tile kt may be refilled
+                asm volatile("s_waitcnt vmcnt(0) lgkmcnt(0)\n\ts_barrier" ::: "memory");
+                if (kt + 2 < nk) issue(kt + 2, kt & 1);
+            }
+            {
+                // on the last tile the positions beyond it read the idle stage: valid LDS, values unused
+                // (drained by the wait after the loop)
+                if constexpr (g + D < G) fetch(std::integral_constant<int, g + D>{}, ca, cw);
+                else fetch(std::integral_constant<int, g + D - G>{}, na, nw);
+                __builtin_amdgcn_sched_barrier(0);
+                // reads issued after position g's: one per later position, plus the activation fragments
+                // of a k-step that starts among them
+                constexpr int later = D + (((g + D) / NI) != (g / NI) ? MI : 0);
+                if constexpr (g % NI == 0) wait_frags<later, MI>(fw[g % R], fa[(g / NI) & 1]);
+                else wait_frag<later>(fw[g % R]);
+                static_for<0, MI>([&](auto jc) {
+                    constexpr int j = decltype(jc)::value;
+                    acc[g % NI][j] = __builtin_amdgcn_mfma_f32_16x16x32_bf16(__builtin_bit_cast(bf16x8, fw[g % R]),
+                                                                             __builtin_bit_cast(bf16x8, fa[(g / NI) & 1][j]),
+                                                                             acc[g % NI][j], 0, 0, 0);
+                });
+                __builtin_amdgcn_sched_barrier(0);
+            }
+        });
+    }
+    wait_lgkmcnt<0>();                              // the last tile's look-ahead reads
 
     // ---- epilogue through LDS: acc[i][j][r] is (m = j*16 + l16, n = i*16 + 4*quarter + r) of the wave tile
     __syncthreads();
