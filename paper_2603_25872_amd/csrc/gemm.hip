@@ -197,8 +197,9 @@ template <int I, int N, typename F> __device__ __forceinline__ void static_for(F
 // block is a whole number of 256-tile rounds), 8 waves as WM x WN, wave tile (BM/WM) x
 // (BN/WN) built from 16x16x32 MFMAs so that widths only need to be multiples of 16.
 //  - operands go HBM -> LDS directly (global_load_lds_dwordx4: every lane supplies its own
-//    global address and the wave's 64 x 16 bytes land contiguously in LDS), two stages, so
-//    the copy of k-tile t+1 overlaps the MFMAs of k-tile t.  A tile row is 128 bytes = 8
+//    global address and the wave's 64 x 16 bytes land contiguously in LDS), NS stages (two
+//    for the wide tiles: all that 160 KB of LDS hold), so the copy of the next k-tiles overlaps
+//    the MFMAs of k-tile t.  A tile row is 128 bytes = 8
 //    chunks; chunk c of row r sits at position c ^ ((r / 2) % 8), which keeps both the DMA
 //    writes and the ds_read_b128 operand fetches free of bank conflicts;
 //  - workgroup ids are remapped so that each XCD (ids are dealt round-robin over the 8 XCDs)
@@ -290,7 +291,7 @@ gemm_bf16_xl_kernel(const bf16_t* __restrict__ A, const bf16_t* __restrict__ W, 
     // with LDS-DMA in the loop the compiler's own wait insertion falls back to lgkmcnt(0), which
     // exposes a full LDS round trip several times per tile.  LDS reads return in order, so before the
     // MFMAs of group g it is enough that at most the reads issued after position g's remain.
-    static_assert(NS == 2 && KS == 2, "the pipelined loop assumes two LDS stages of two k-steps");
+    static_assert(NS >= 2 && KS == 2, "the pipelined loop assumes LDS stages of two k-steps");
     constexpr int G = KS * NI;
     constexpr int R = G % 6 == 0 ? 6 : G % 4 == 0 ? 4 : G % 5 == 0 ? 5 : G % 3 == 0 ? 3 : 2, D = R - 1;
     static_assert(G % R == 0 && D < NI && D + MI <= 15, "ring size");
@@ -314,12 +315,19 @@ gemm_bf16_xl_kernel(const bf16_t* __restrict__ A, const bf16_t* __restrict__ W, 
         lds_read16<i * 16 * BK * 2>(fw[p % R], wa[ks]);
     };
 
+    // tiles 0 .. NS-2 are in flight before the loop; tile kt + NS - 1 is requested once tile kt - 1 has been read
     issue(0, 0);
-    asm volatile("s_waitcnt vmcnt(0)\n\ts_barrier" ::: "memory");
-    if (1 < nk) issue(1, 1);
+#pragma unroll
+    for (int t = 1; t < NS - 1; ++t)
+        if (t < nk) issue(t, t);
+    if (NS > 2 && nk >= NS - 1) wait_vmcnt<LPT * (NS - 2)>(); else wait_vmcnt<0>();
+    asm volatile("s_barrier" ::: "memory");
+    if (NS - 1 < nk) issue(NS - 1, NS - 1);
     static_for<0, D>([&](auto pc) { fetch(pc, a_addr, w_addr); });
+    int cs = 0;                                     // stage of tile kt
     for (int kt = 0; kt < nk; ++kt) {
-        const uint32_t co = (uint32_t)(kt & 1) * (uint32_t)(STAGE * 2), no = (uint32_t)(STAGE * 2) - co;
+        const int ns = cs + 1 == NS ? 0 : cs + 1;
+        const uint32_t co = (uint32_t)cs * (uint32_t)(STAGE * 2), no = (uint32_t)ns * (uint32_t)(STAGE * 2);
         uint32_t ca[KS], cw[KS], na[KS], nw[KS];
 #pragma unroll
         for (int ks = 0; ks < KS; ++ks) { ca[ks] = a_addr[ks] + co; cw[ks] = w_addr[ks] + co; na[ks] = a_addr[ks] + no; nw[ks] = w_addr[ks] + no; }
@@ -328,8 +336,10 @@ gemm_bf16_xl_kernel(const bf16_t* __restrict__ A, const bf16_t* __restrict__ W, 
             if constexpr (g + D == G) {
                 // tile kt+1 has landed (vmcnt 0) and this wave's reads of tile kt are complete (lgkmcnt 0), for
                 // every wave after the barrier: the stage of tile kt may be refilled
-                asm volatile("s_waitcnt vmcnt(0) lgkmcnt(0)\n\ts_barrier" ::: "memory");
-                if (kt + 2 < nk) issue(kt + 2, kt & 1);
+                // (the NS - 2 younger tiles may still be in flight; near the end fewer are, so wait for all)
+                if (NS > 2 && kt + NS - 1 < nk) wait_vmcnt<LPT * (NS - 2)>(); else wait_vmcnt<0>();
+                asm volatile("s_waitcnt lgkmcnt(0)\n\ts_barrier" ::: "memory");
+                if (kt + NS < nk) issue(kt + NS, cs);
             }
             {
                 // on the last tile the positions beyond it read the idle stage: valid LDS, values unused
@@ -351,6 +361,7 @@ gemm_bf16_xl_kernel(const bf16_t* __restrict__ A, const bf16_t* __restrict__ W, 
                 __builtin_amdgcn_sched_barrier(0);
             }
         });
+        cs = ns;
     }
     wait_lgkmcnt<0>();                              // the last tile's look-ahead reads
 
@@ -596,7 +607,7 @@ drf_status launch_gemm_bf16(const bf16_t* A, const bf16_t* W, int M, int N, int 
     case 4: return launch_bf16_xl<128, 288, 64, 2, 2, 2>(A, W, M, N, K, e, st);
     case 5: return launch_bf16_xl<128, 128, 64, 2, 2, 2>(A, W, M, N, K, e, st);
     case 6: return launch_bf16_xl<256, 288, 64, 2, 4, 3>(A, W, M, N, K, e, st);
-    case 7: return launch_bf16_xl<128, 144, 64, 2, 4, 1>(A, W, M, N, K, e, st);
+    case 7: return launch_bf16_xl<128, 144, 64, 4, 4, 1>(A, W, M, N, K, e, st);
     case 8: return launch_bf16_xl<128, 144, 64, 2, 4, 1, 2>(A, W, M, N, K, e, st);
     default: return launch_bf16_tile<128, 128, 2, 2>(A, W, M, N, K, e, st);
     }
