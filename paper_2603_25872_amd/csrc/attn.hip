@@ -3,6 +3,8 @@
 // (S^T = K Q^T) so that each lane owns one query column and the online softmax needs a
 // single cross-lane exchange; P^T feeds the second MFMA straight from registers.
 // fp32 path: one thread per query, for the fp32 configuration.
+#include <type_traits>
+
 #include "common.h"
 
 namespace drf {
@@ -13,8 +15,7 @@ typedef bf16_t bf16x8 __attribute__((ext_vector_type(8)));
 typedef bf16_t bf16x4 __attribute__((ext_vector_type(4)));
 typedef float f32x16 __attribute__((ext_vector_type(16)));
 
-constexpr int kKvb = 64;            // kv rows staged per step
-constexpr int kQPerBlock = 128;     // 4 waves x 32 queries
+constexpr int kKvb = 64;            // kv rows per online-softmax step
 // max of three without the canonicalisation the generic fmaxf lowering adds per operand
 __device__ inline float max3(float a, float b, float c)
 {
@@ -24,37 +25,50 @@ __device__ inline float max3(float a, float b, float c)
 }
 constexpr float kTau = 8.f;         // lazy-rescale headroom of the online softmax, in log2 units
 
-// KS = ceil(d / 16) k-steps of the score MFMA; DT = ceil(d / 32) row tiles of O^T.
+// KS = ceil(d / 16) k-steps of the score MFMA; DT = ceil(d / 32) row tiles of O^T; NW waves of 32
+// queries per block, all sharing the staged K / V (NW = 8 covers the 256 tokens of a DiT-XL head
+// with one block, so K and V are read and transposed once per head).
+// K and V^T are staged in chunks of KC kv rows, NB chunk buffers: a sequence of up to KC rows is
+// staged once (NB = 1) and the waves then run their steps without any block barrier; longer
+// sequences alternate two buffers with one barrier per chunk.  Between barriers the two waves of
+// a SIMD drift apart, so the MFMAs of one overlap the softmax arithmetic of the other; a barrier
+// per 64-row step would keep every wave in the same phase and leave either the matrix or the
+// vector unit idle.
 // Per step 64 kv rows: two 32 x 32 score tiles, one online-softmax update, four PV k-chunks.
-// The next K/V tile is fetched into registers while the current one is being used.
-template <int KS, int DT>
-__global__ void __launch_bounds__(256) attn_bf16_kernel(const AttnArgs a, float scale_log2)
+// V^T is stored with the 16 kv rows of each k-chunk permuted to [0-3, 8-11 | 4-7, 12-15]: that is
+// the order in which the score MFMA leaves a lane's P values, so the PV operand is one 16-byte read,
+// and the transposing store of four kv rows of one d is one 8-byte write.
+template <int KS, int DT, int NW, int KC, int NB>
+__global__ void __launch_bounds__(NW * 64) attn_bf16_kernel(const AttnArgs a, float scale_log2)
 {
-    constexpr int DK = KS * 16, LDKS = DK + 8, LDV = kKvb + 8;
-    constexpr int MAXCH = (kKvb * (KS * 2) + 255) / 256;                   // 16-byte chunks of a tile per thread
-    __shared__ __attribute__((aligned(16))) bf16_t sK[kKvb * LDKS];        // [kv][d padded]
-    __shared__ __attribute__((aligned(16))) bf16_t sVt[DT * 32 * LDV];      // [d padded][kv]
+    constexpr int NT = NW * 64;
+    constexpr int DK = KS * 16, LDKS = DK + 8, LDV = KC + 8;
+    constexpr int KBUF = KC * LDKS, VBUF = DT * 32 * LDV;
+    constexpr int MAXK = (KC * (KS * 2) + NT - 1) / NT;                   // 16-byte K pieces of a chunk per thread
+    constexpr int MAXV = ((KC / 4) * (KS * 2) + NT - 1) / NT;             // (4 kv rows x 8 d) V blocks per thread
+    extern __shared__ __attribute__((aligned(16))) unsigned char attn_smem[];
+    bf16_t* sK = reinterpret_cast<bf16_t*>(attn_smem);                    // [buf][kv][d padded]
+    bf16_t* sVt = sK + NB * KBUF;                                         // [buf][d padded][kv, permuted]
     const int tid = threadIdx.x, lane = tid & 63, wave = tid >> 6, l32 = lane & 31, half = lane >> 5;
     const int slot = blockIdx.z, h = blockIdx.y, d = a.d;
     const int kvb = a.kv_mod ? slot % a.kv_mod : slot;
     const bf16_t* Q = (const bf16_t*)a.q + slot * a.q_slot_stride + h * a.q_head_stride;
     const bf16_t* Kp = (const bf16_t*)a.k + kvb * a.kv_batch_stride + h * a.kv_head_stride;
     const bf16_t* Vp = (const bf16_t*)a.v + kvb * a.kv_batch_stride + h * a.kv_head_stride;
+    const bf16x8 zero8 = { 0, 0, 0, 0, 0, 0, 0, 0 };
 
     // zero the padding that loads never touch: K columns [d, DK), V^T rows [d, DT*32)
-    for (int i = tid; i < kKvb * LDKS; i += 256) sK[i] = (bf16_t)0.f;
-    for (int i = tid; i < DT * 32 * LDV; i += 256) sVt[i] = (bf16_t)0.f;
+    for (int i = tid; i < NB * (KBUF + VBUF) / 8; i += NT) reinterpret_cast<bf16x8*>(sK)[i] = zero8;
     // When the head width leaves a padding row in O^T, V^T row d is set to ones: the PV MFMA
     // then accumulates the softmax denominator there for free.
     const bool ones_row = d < DT * 32;
     __syncthreads();
     if (ones_row)
-        for (int i = tid; i < LDV; i += 256) sVt[d * LDV + i] = (bf16_t)1.f;
+        for (int i = tid; i < NB * LDV; i += NT) sVt[(i / LDV) * VBUF + d * LDV + i % LDV] = (bf16_t)1.f;
 
     // this lane's query column and its Q fragments (B operand: 8 consecutive d per k-step half)
-    const int q = blockIdx.x * kQPerBlock + wave * 32 + l32;
+    const int q = blockIdx.x * (NW * 32) + wave * 32 + l32;
     const int qc = q < a.Nq ? q : a.Nq - 1;
-    const bf16x8 zero8 = { 0, 0, 0, 0, 0, 0, 0, 0 };
     bf16x8 qf[KS];
 #pragma unroll
     for (int ks = 0; ks < KS; ++ks) {
@@ -67,56 +81,84 @@ __global__ void __launch_bounds__(256) attn_bf16_kernel(const AttnArgs a, float 
 #pragma unroll
         for (int r = 0; r < 16; ++r) o[t][r] = 0.f;
     float m_run = -INFINITY, l_run = 0.f;      // running max of the raw scores, running sum
-    const int dch = d / 8, nch = kKvb * dch;    // 16-byte chunks per row / per tile
+    const int dch = d / 8, nch = KC * dch, nvb = (KC / 4) * dch;
 
-    // K chunks: consecutive threads take consecutive 16-byte chunks of a row (coalesced loads,
-    // 16-byte LDS writes).  V chunks: consecutive threads take consecutive kv rows of one chunk
-    // column, so that the transposing 2-byte LDS writes of a wave fall on consecutive addresses.
-    bf16x8 rk[MAXCH], rv[MAXCH];
+    // K: consecutive threads take consecutive 16-byte pieces of a row (coalesced loads, 16-byte LDS
+    // writes).  V: a thread takes 4 consecutive kv rows of one 8-wide d piece and writes, for each
+    // of the 8 d, the 4 kv values as one 8-byte piece of the V^T row.
+    bf16x8 rk[MAXK], rv[MAXV][4];
     auto fetch = [&](int kv0) {
 #pragma unroll
-        for (int c = 0; c < MAXCH; ++c) {
-            const int id = tid + c * 256;
-            const int rk_r = id / dch, rk_c = id % dch, rv_c = id / kKvb, rv_r = id % kKvb;
-            rk[c] = zero8; rv[c] = zero8;
-            if (id < nch) {
-                if (kv0 + rk_r < a.Nk) rk[c] = *reinterpret_cast<const bf16x8*>(Kp + (size_t)(kv0 + rk_r) * a.ldk + rk_c * 8);
-                if (kv0 + rv_r < a.Nk) rv[c] = *reinterpret_cast<const bf16x8*>(Vp + (size_t)(kv0 + rv_r) * a.ldk + rv_c * 8);
+        for (int c = 0; c < MAXK; ++c) {
+            const int id = tid + c * NT, r = id / dch, cc = id % dch;
+            rk[c] = zero8;
+            if (id < nch && kv0 + r < a.Nk) rk[c] = *reinterpret_cast<const bf16x8*>(Kp + (size_t)(kv0 + r) * a.ldk + cc * 8);
+        }
+#pragma unroll
+        for (int c = 0; c < MAXV; ++c) {
+            const int id = tid + c * NT, g4 = id % (KC / 4), cc = id / (KC / 4);
+#pragma unroll
+            for (int j = 0; j < 4; ++j) {
+                rv[c][j] = zero8;
+                if (id < nvb && kv0 + 4 * g4 + j < a.Nk)
+                    rv[c][j] = *reinterpret_cast<const bf16x8*>(Vp + (size_t)(kv0 + 4 * g4 + j) * a.ldk + cc * 8);
             }
         }
     };
-    auto stage = [&]() {
+    auto stage = [&](int buf) {
+        bf16_t* bk = sK + buf * KBUF;
+        bf16_t* bv = sVt + buf * VBUF;
 #pragma unroll
-        for (int c = 0; c < MAXCH; ++c) {
-            const int id = tid + c * 256;
-            const int rk_r = id / dch, rk_c = id % dch, rv_c = id / kKvb, rv_r = id % kKvb;
-            if (id < nch) {
-                *reinterpret_cast<bf16x8*>(sK + rk_r * LDKS + rk_c * 8) = rk[c];
+        for (int c = 0; c < MAXK; ++c) {
+            const int id = tid + c * NT, r = id / dch, cc = id % dch;
+            if (id < nch) *reinterpret_cast<bf16x8*>(bk + r * LDKS + cc * 8) = rk[c];
+        }
 #pragma unroll
-                for (int e = 0; e < 8; ++e) sVt[(rv_c * 8 + e) * LDV + rv_r] = rv[c][e];
+        for (int c = 0; c < MAXV; ++c) {
+            const int id = tid + c * NT, g4 = id % (KC / 4), cc = id / (KC / 4);
+            // kv rows 4 g4 .. 4 g4 + 3 of the chunk: position of row r16 inside its 16-row group is
+            // 8 * ((r16 >> 2) & 1) + (r16 & 3) + 4 * (r16 >> 3)
+            const int k4 = g4 & 3, pos = 16 * (g4 >> 2) + 8 * (k4 & 1) + 4 * (k4 >> 1);
+            if (id < nvb) {
+#pragma unroll
+                for (int e = 0; e < 8; ++e) {
+                    const bf16x4 w = { rv[c][0][e], rv[c][1][e], rv[c][2][e], rv[c][3][e] };
+                    *reinterpret_cast<bf16x4*>(bv + (cc * 8 + e) * LDV + pos) = w;
+                }
             }
         }
     };
 
-    fetch(0);
-    for (int kv0 = 0; kv0 < a.Nk; kv0 += kKvb) {
-        __syncthreads();                    // previous tile fully consumed (and zero fill done)
-        stage();
-        __syncthreads();
-        if (kv0 + kKvb < a.Nk) fetch(kv0 + kKvb);
-        // S^T[kv][q] = sum_d K[kv][d] Q[q][d] for the two 32-row halves of the tile
+    // one online-softmax step over the 64 kv rows at row `row0` of a staged chunk (global row kv0)
+    auto step = [&](const bf16_t* bk, const bf16_t* bv, int row0, int kv0) {
+        // S^T[kv][q] = sum_d K[kv][d] Q[q][d] for the two 32-row halves.  All K fragments of the step
+        // are requested before the first MFMA, and the V^T fragments right after the score MFMAs, so
+        // that they land while the softmax runs.
+        bf16x8 kf[2][KS];
+#pragma unroll
+        for (int t = 0; t < 2; ++t)
+#pragma unroll
+            for (int ks = 0; ks < KS; ++ks)
+                kf[t][ks] = *reinterpret_cast<const bf16x8*>(bk + (row0 + t * 32 + l32) * LDKS + ks * 16 + half * 8);
         f32x16 s[2];
 #pragma unroll
         for (int t = 0; t < 2; ++t) {
             const f32x16 zero16 = { 0.f, 0.f, 0.f, 0.f, 0.f, 0.f, 0.f, 0.f, 0.f, 0.f, 0.f, 0.f, 0.f, 0.f, 0.f, 0.f };
 #pragma unroll
-            for (int ks = 0; ks < KS; ++ks) {
-                bf16x8 kf = *reinterpret_cast<const bf16x8*>(sK + (t * 32 + l32) * LDKS + ks * 16 + half * 8);
-                s[t] = __builtin_amdgcn_mfma_f32_32x32x16_bf16(kf, qf[ks], ks == 0 ? zero16 : s[t], 0, 0, 0);
-            }
+            for (int ks = 0; ks < KS; ++ks)
+                s[t] = __builtin_amdgcn_mfma_f32_32x32x16_bf16(kf[t][ks], qf[ks], ks == 0 ? zero16 : s[t], 0, 0, 0);
         }
-        // register r of s[t] holds kv row t*32 + 8*(r/4) + 4*half + r%4 of the tile
-        if (kv0 + kKvb > a.Nk) {            // ragged last tile: rows past the end do not take part
+        bf16x8 vf[2][2][DT];
+#pragma unroll
+        for (int t = 0; t < 2; ++t)
+#pragma unroll
+            for (int c = 0; c < 2; ++c)
+#pragma unroll
+                for (int tt = 0; tt < DT; ++tt)
+                    vf[t][c][tt] = *reinterpret_cast<const bf16x8*>(bv + (tt * 32 + l32) * LDV + row0 + t * 32 + 16 * c + 8 * half);
+        __builtin_amdgcn_sched_barrier(0);
+        // register r of s[t] holds kv row t*32 + 8*(r/4) + 4*half + r%4 of the step
+        if (kv0 + kKvb > a.Nk) {            // ragged last step: rows past the end do not take part
 #pragma unroll
             for (int t = 0; t < 2; ++t)
 #pragma unroll
@@ -132,7 +174,7 @@ __global__ void __launch_bounds__(256) attn_bf16_kernel(const AttnArgs a, float 
         // bf16 operands and fp32 sums) and the accumulators need no rescale.
         if (__any((mx - m_run) * scale_log2 > kTau)) {
             const float m_new = fmaxf(m_run, mx);
-            const float alpha = __builtin_amdgcn_exp2f((m_run - m_new) * scale_log2);   // 0 on the first tile
+            const float alpha = __builtin_amdgcn_exp2f((m_run - m_new) * scale_log2);   // 0 on the first step
             m_run = m_new;
             l_run *= alpha;
 #pragma unroll
@@ -152,7 +194,8 @@ __global__ void __launch_bounds__(256) attn_bf16_kernel(const AttnArgs a, float 
             l_run += psum;                  // this half's share; the halves are added at the end
         }
         // O^T[d][q] += sum_kv V^T[d][kv] P^T[kv][q]; element e of a lane's k-slice is kv row
-        // 16c + 4*half + e (e < 4) or 16c + 8 + 4*half + e - 4 of the 32-row half, for both operands.
+        // 16c + 4*half + e (e < 4) or 16c + 8 + 4*half + e - 4 of the 32-row half, for both operands:
+        // in the permuted V^T row these are the 8 consecutive values at 16c + 8*half.
 #pragma unroll
         for (int t = 0; t < 2; ++t)
 #pragma unroll
@@ -161,14 +204,34 @@ __global__ void __launch_bounds__(256) attn_bf16_kernel(const AttnArgs a, float 
 #pragma unroll
                 for (int e2 = 0; e2 < 8; ++e2) pf[e2] = (bf16_t)s[t][8 * c + e2];
 #pragma unroll
-                for (int tt = 0; tt < DT; ++tt) {
-                    const bf16_t* vp = sVt + (tt * 32 + l32) * LDV + t * 32 + 16 * c + 4 * half;
-                    bf16x4 v0 = *reinterpret_cast<const bf16x4*>(vp);
-                    bf16x4 v1 = *reinterpret_cast<const bf16x4*>(vp + 8);
-                    bf16x8 vf = __builtin_shufflevector(v0, v1, 0, 1, 2, 3, 4, 5, 6, 7);
-                    o[tt] = __builtin_amdgcn_mfma_f32_32x32x16_bf16(vf, pf, o[tt], 0, 0, 0);
-                }
+                for (int tt = 0; tt < DT; ++tt) o[tt] = __builtin_amdgcn_mfma_f32_32x32x16_bf16(vf[t][c][tt], pf, o[tt], 0, 0, 0);
             }
+    };
+
+    fetch(0);
+    __syncthreads();                            // zero fill and ones row done
+    stage(0);
+    __syncthreads();
+    int buf = 0;
+    for (int c0 = 0; c0 < a.Nk; c0 += KC) {
+        // chunk c0 is visible in `buf`; with two buffers the next chunk is fetched now and staged
+        // after this chunk's steps (the other buffer was last read before the previous barrier)
+        const bool more = c0 + KC < a.Nk;
+        if (NB == 2 && more) fetch(c0 + KC);
+        const bf16_t* bk = sK + buf * KBUF;
+        const bf16_t* bv = sVt + buf * VBUF;
+        for (int r0 = 0; r0 < KC && c0 + r0 < a.Nk; r0 += kKvb) step(bk, bv, r0, c0 + r0);
+        if (more) {
+            if (NB == 2) {
+                stage(buf ^ 1);
+                buf ^= 1;
+            } else {                            // single buffer: refill in place
+                __syncthreads();
+                fetch(c0 + KC);
+                stage(0);
+            }
+            __syncthreads();
+        }
     }
     // denominator: from the ones row (kept by the lanes of one half) or the two halves' partial sums
     float l_tot;
@@ -230,13 +293,35 @@ __global__ void __launch_bounds__(128) attn_f32_kernel(const AttnArgs a, float s
     for (int e = 0; e < d; ++e) op[e] = o[e] * inv;
 }
 
+template <int KS, int DT, int NW, int KC, int NB>
+drf_status launch_bf16_cfg(const AttnArgs& a, float scale_log2, hipStream_t st)
+{
+    constexpr int LDKS = KS * 16 + 8, LDV = KC + 8;
+    constexpr size_t smem = (size_t)NB * (KC * LDKS + DT * 32 * LDV) * sizeof(bf16_t);
+    static_assert(smem <= 160 * 1024 && smem % 16 == 0, "LDS budget");
+    auto kern = attn_bf16_kernel<KS, DT, NW, KC, NB>;
+    static bool attr_set = false;
+    if (!attr_set) {
+        DRF_HIP(hipFuncSetAttribute(reinterpret_cast<const void*>(kern), hipFuncAttributeMaxDynamicSharedMemorySize, (int)smem));
+        attr_set = true;
+    }
+    const dim3 grid((a.Nq + NW * 32 - 1) / (NW * 32), a.heads, a.slots);
+    hipLaunchKernelGGL(kern, grid, dim3(NW * 64), smem, st, a, scale_log2);
+    DRF_HIP(hipGetLastError());
+    return DRF_OK;
+}
+
 template <int KS, int DT>
 drf_status launch_bf16_inst(const AttnArgs& a, float scale_log2, hipStream_t st)
 {
-    const dim3 grid((a.Nq + kQPerBlock - 1) / kQPerBlock, a.heads, a.slots);
-    hipLaunchKernelGGL((attn_bf16_kernel<KS, DT>), grid, dim3(256), 0, st, a, scale_log2);
-    DRF_HIP(hipGetLastError());
-    return DRF_OK;
+    // 8 waves (256 queries) share each staged chunk when there are that many queries; a sequence of
+    // up to 256 kv rows is staged whole, longer ones in double-buffered chunks of 128
+    if (a.Nq > 128) {
+        if (a.Nk <= 256) return launch_bf16_cfg<KS, DT, 8, 256, 1>(a, scale_log2, st);
+        return launch_bf16_cfg<KS, DT, 8, 128, 2>(a, scale_log2, st);
+    }
+    if (a.Nk <= 256) return launch_bf16_cfg<KS, DT, 4, 256, 1>(a, scale_log2, st);
+    return launch_bf16_cfg<KS, DT, 4, 128, 2>(a, scale_log2, st);
 }
 
 }  // namespace
