@@ -208,6 +208,60 @@ __global__ void __launch_bounds__(256) ln_modulate_kernel(const float* __restric
     }
 }
 
+// Same operation for hidden sizes that are multiples of 128: half a wave per row, 16-byte loads
+// of the residual row (PER4 float4 per lane) and 8-byte (bf16) or 16-byte (fp32) stores.
+__device__ inline float half_wave_sum(float v)
+{
+#pragma unroll
+    for (int o = 16; o >= 1; o >>= 1) v += __shfl_xor(v, o, 64);
+    return v;
+}
+template <int PER4, typename OutT>
+__global__ void __launch_bounds__(256) ln_modulate4_kernel(const float* __restrict__ resid, const float* __restrict__ shift,
+                                                           const float* __restrict__ scale, int mod_ld, int rows_per_slot,
+                                                           int M, OutT* __restrict__ out)
+{
+    constexpr int D = PER4 * 128;
+    const int l32 = threadIdx.x & 31, row = blockIdx.x * (blockDim.x >> 5) + (threadIdx.x >> 5);
+    if (row >= M) return;                       // M is even here or the spare half wave idles: no block barrier below
+    const float4* xr = reinterpret_cast<const float4*>(resid + (size_t)row * D);
+    float4 v[PER4];
+    float sum = 0.f;
+#pragma unroll
+    for (int i = 0; i < PER4; ++i) {
+        v[i] = xr[i * 32 + l32];
+        sum += (v[i].x + v[i].y) + (v[i].z + v[i].w);
+    }
+    const float mean = half_wave_sum(sum) * (1.f / (float)D);
+    float sq = 0.f;
+#pragma unroll
+    for (int i = 0; i < PER4; ++i) {
+        const float dx = v[i].x - mean, dy = v[i].y - mean, dz = v[i].z - mean, dw = v[i].w - mean;
+        sq = fmaf(dx, dx, fmaf(dy, dy, fmaf(dz, dz, fmaf(dw, dw, sq))));
+    }
+    const float rstd = rsqrtf(half_wave_sum(sq) * (1.f / (float)D) + 1e-6f);
+    const size_t mrow = (size_t)(row / rows_per_slot) * mod_ld;
+    const float4* sh = shift ? reinterpret_cast<const float4*>(shift + mrow) : nullptr;
+    const float4* sc = shift ? reinterpret_cast<const float4*>(scale + mrow) : nullptr;
+#pragma unroll
+    for (int i = 0; i < PER4; ++i) {
+        const int j = i * 32 + l32;
+        float y0 = (v[i].x - mean) * rstd, y1 = (v[i].y - mean) * rstd, y2 = (v[i].z - mean) * rstd, y3 = (v[i].w - mean) * rstd;
+        if (sh) {
+            const float4 s4 = sc[j], h4 = sh[j];
+            y0 = fmaf(y0, 1.f + s4.x, h4.x); y1 = fmaf(y1, 1.f + s4.y, h4.y);
+            y2 = fmaf(y2, 1.f + s4.z, h4.z); y3 = fmaf(y3, 1.f + s4.w, h4.w);
+        }
+        if constexpr (sizeof(OutT) == 4) {
+            reinterpret_cast<float4*>(out + (size_t)row * D)[j] = make_float4(y0, y1, y2, y3);
+        } else {
+            typedef bf16_t bf16x4 __attribute__((ext_vector_type(4)));
+            const bf16x4 o = { (bf16_t)y0, (bf16_t)y1, (bf16_t)y2, (bf16_t)y3 };
+            reinterpret_cast<bf16x4*>(out + (size_t)row * D)[j] = o;
+        }
+    }
+}
+
 // Final layer: LN + modulate, Linear(D -> P), scatter to [C][H][W].  A block of 4 waves takes
 // kFinalRowsPerBlock token rows; wave w keeps the weights of outputs w, w+4, w+8, w+12 (of each
 // group of 16) in registers and sweeps the rows, so nothing but the residual rows is re-read.
@@ -334,11 +388,37 @@ static void launch_ln_inst(const float* resid, const float* shift, const float* 
                            M, D, (bf16_t*)out);
 }
 
+template <int PER4>
+void launch_ln4_inst(const float* resid, const float* shift, const float* scale, int mod_ld, int rows_per_slot, int M,
+                     void* out, int out_f32, hipStream_t st)
+{
+    const dim3 grid((M + 7) / 8), block(256);
+    if (out_f32)
+        hipLaunchKernelGGL((ln_modulate4_kernel<PER4, float>), grid, block, 0, st, resid, shift, scale, mod_ld, rows_per_slot, M,
+                           (float*)out);
+    else
+        hipLaunchKernelGGL((ln_modulate4_kernel<PER4, bf16_t>), grid, block, 0, st, resid, shift, scale, mod_ld, rows_per_slot,
+                           M, (bf16_t*)out);
+}
+
 drf_status launch_ln_modulate(const float* resid, const float* shift, const float* scale, int mod_ld, int rows_per_slot,
                               int M, int D, void* out, int out_f32, hipStream_t st)
 {
     if (M == 0) return DRF_OK;
     if (D > 2048 || D % 2 != 0 || mod_ld % 2 != 0) DRF_FAIL(DRF_ESHAPE, "LayerNorm kernel needs even hidden <= 2048 (got %d)", D);
+    const bool al16 = mod_ld % 4 == 0 && ((reinterpret_cast<uintptr_t>(resid) | reinterpret_cast<uintptr_t>(out) |
+                                           reinterpret_cast<uintptr_t>(shift) | reinterpret_cast<uintptr_t>(scale)) & 15u) == 0;
+    if (al16 && (D == 1152 || D == 384 || D == 768 || D == 1024 || D == 128)) {
+        switch (D / 128) {
+        case 1: launch_ln4_inst<1>(resid, shift, scale, mod_ld, rows_per_slot, M, out, out_f32, st); break;
+        case 3: launch_ln4_inst<3>(resid, shift, scale, mod_ld, rows_per_slot, M, out, out_f32, st); break;
+        case 6: launch_ln4_inst<6>(resid, shift, scale, mod_ld, rows_per_slot, M, out, out_f32, st); break;
+        case 8: launch_ln4_inst<8>(resid, shift, scale, mod_ld, rows_per_slot, M, out, out_f32, st); break;
+        default: launch_ln4_inst<9>(resid, shift, scale, mod_ld, rows_per_slot, M, out, out_f32, st); break;
+        }
+        DRF_HIP(hipGetLastError());
+        return DRF_OK;
+    }
     const int per = (D / 2 + kWave - 1) / kWave;      // column pairs per lane
     if (per <= 1) launch_ln_inst<1>(resid, shift, scale, mod_ld, rows_per_slot, M, D, out, out_f32, st);
     else if (per <= 3) launch_ln_inst<3>(resid, shift, scale, mod_ld, rows_per_slot, M, D, out, out_f32, st);
