@@ -237,9 +237,9 @@ class Denoiser:
         self.h = h
 
     def close(self):
-        if getattr(self, "h", None):
-            lib().drf_denoiser_destroy(self.h)
-            self.h = None
+        h, self.h = getattr(self, "h", None), None
+        if h and _lib is not None:              # at interpreter exit the module may already be torn down
+            _lib.drf_denoiser_destroy(h)
 
     __del__ = close
 
