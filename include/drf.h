@@ -88,8 +88,10 @@ typedef enum { DRF_DDIM = 0, DRF_DDPM = 1, DRF_EULER = 2 } drf_sampler;
  *   (shift, scale) = Linear(D->2D)(SiLU(c)); eps tokens = Linear(D->P)(LN(h)(1+scale)+shift),
  *   scattered back to [in_ch][lat_h][lat_w].  LN has no affine, eps 1e-6.
  * dtype DRF_BF16: every parameter is rounded to bf16 (round-to-nearest-even) once at
- * create; GEMM and attention operands are bf16 with fp32 accumulation; LayerNorm and
- * softmax statistics, the residual stream, latents and all sampler updates are fp32.
+ * create; GEMM and attention operands are bf16 with fp32 accumulation; the gated branch
+ * outputs (attention projection, MLP) are rounded to bf16 before they are added to the
+ * residual stream; LayerNorm and softmax statistics, the residual stream itself, latents
+ * and all sampler updates are fp32.
  * dtype DRF_F32: everything in fp32.
  * Requirements: hidden % heads == 0, hidden % 4 == 0, lat_h, lat_w % patch == 0;
  * DRF_BF16 also needs hidden % 64 == 0, d % 8 == 0, d <= 96, cond_dim % 64 == 0 for text.

@@ -94,14 +94,16 @@ struct SlotMap {
     int cond_mod;           // cond row of slot j = cond_mod ? j % cond_mod : j
 };
 
-enum EpiMode { EPI_STORE = 0, EPI_STORE_GELU = 1, EPI_RESID = 2, EPI_STORE_HEADS = 3 };
+enum EpiMode { EPI_STORE = 0, EPI_STORE_GELU = 1, EPI_RESID = 2, EPI_STORE_HEADS = 3, EPI_STORE_GATED = 4 };
 struct Epilogue {
     int mode;
     void* out;              // EPI_STORE*: [M][ldo] of out type; EPI_RESID: float [M][ldo], read-modify-write
     int ldo;
     int out_f32;            // EPI_STORE*: 1 = float output, 0 = bf16 output
     const float* bias;      // [N]
-    const float* gate;      // EPI_RESID: gate[(m / rows_per_slot) * gate_ld + n], NULL = ungated
+    const float* gate;      // EPI_RESID, EPI_STORE_GATED: gate[(m / rows_per_slot) * gate_ld + n]; EPI_RESID: NULL = ungated
+                            // EPI_STORE_GATED (bf16 only): out = gate * (acc + bias), the branch output that the next
+                            // LayerNorm launch adds to the residual stream
     int gate_ld, rows_per_slot;
     uint32_t rps_magic; int rps_shift;   // m / rows_per_slot == fast_div(m, rps_magic, rps_shift), see set_rows_per_slot
     // EPI_STORE_HEADS (bf16 only): column n = which * hid + head * hd + dd of row m = slot * rows_per_slot + t goes to
@@ -147,8 +149,9 @@ drf_status launch_cond_embed(const CondArgs& a, hipStream_t st);
 drf_status launch_patch_embed(const float* x, const SlotMap& map, const float* w, const float* b, const float* pos,
                               const DitDims& dm, int slots, float* resid, hipStream_t st);
 // out = LN(resid) * (1 + scale) + shift (shift == NULL: plain LN); mod rows are per slot.
-drf_status launch_ln_modulate(const float* resid, const float* shift, const float* scale, int mod_ld, int rows_per_slot,
-                              int M, int D, void* out, int out_f32, hipStream_t st);
+// add != NULL (bf16 [M][D]): resid += add first, and the updated residual rows are written back.
+drf_status launch_ln_modulate(float* resid, const bf16_t* add, const float* shift, const float* scale, int mod_ld,
+                              int rows_per_slot, int M, int D, void* out, int out_f32, hipStream_t st);
 drf_status launch_final(const float* resid, const float* shift, const float* scale, int mod_ld, const float* w,
                         const float* b, const DitDims& dm, int slots, float* eps_out, hipStream_t st);
 drf_status launch_f32_to_bf16(const float* in, bf16_t* out, size_t n, hipStream_t st);

@@ -45,7 +45,7 @@ struct drf_denoiser {
     // workspace
     int cap_slots = 0, cap_cond_rows = 0;
     float *resid = nullptr, *mod = nullptr, *cact32 = nullptr, *cscratch = nullptr;
-    void *hbuf = nullptr, *qkv = nullptr, *mid = nullptr, *cact = nullptr;
+    void *hbuf = nullptr, *qkv = nullptr, *mid = nullptr, *ybuf = nullptr, *cact = nullptr;
     // cross-attention K/V cache [L][rows][ctx_len][2D] and its staging
     void* xkv = nullptr; void* ctx_act = nullptr; int cap_ctx_rows = 0;
     // sampler buffers
@@ -149,7 +149,7 @@ drf_status ensure_workspace(drf_denoiser* d, int slots, hipStream_t st)
 {
     if (slots <= d->cap_slots) return DRF_OK;
     DRF_HIP(hipStreamSynchronize(st));
-    void* olds[] = { d->resid, d->hbuf, d->qkv, d->mid };
+    void* olds[] = { d->resid, d->hbuf, d->qkv, d->mid, d->ybuf };
     for (void* p : olds) dev_free(d, p);
     d->cap_slots = 0;
     const size_t M = (size_t)slots * d->dm.T, D = (size_t)d->dm.D, act = d->bf16 ? 2 : 4;
@@ -158,6 +158,7 @@ drf_status ensure_workspace(drf_denoiser* d, int slots, hipStream_t st)
     if ((rc = dev_alloc(d, &d->hbuf, M * D * act)) != DRF_OK) return rc;
     if ((rc = dev_alloc(d, &d->qkv, M * 3 * D * act)) != DRF_OK) return rc;
     if ((rc = dev_alloc(d, &d->mid, M * (size_t)d->dm.R * D * act)) != DRF_OK) return rc;
+    if ((rc = dev_alloc(d, &d->ybuf, M * D * act)) != DRF_OK) return rc;
     d->cap_slots = slots;
     return DRF_OK;
 }
@@ -217,6 +218,15 @@ Epilogue epi_heads(void* out, int M, const DitDims& dm)
     e.hid = dm.D; e.hd = dm.d; e.heads = dm.heads; e.plane = (size_t)M * dm.D;
     make_fast_div(dm.D, &e.hid_magic, &e.hid_shift);
     make_fast_div(dm.d, &e.hd_magic, &e.hd_shift);
+    return e;
+}
+
+// bf16 branch output gate * (acc + bias), to be added to the residual stream by the next LayerNorm launch
+Epilogue epi_gated(void* out, int ldo, const float* gate, int gate_ld, int rows_per_slot)
+{
+    Epilogue e{};
+    e.mode = EPI_STORE_GATED; e.out = out; e.ldo = ldo; e.out_f32 = 0; e.gate = gate; e.gate_ld = gate_ld;
+    set_rows_per_slot(&e, rows_per_slot);
     return e;
 }
 
@@ -285,13 +295,21 @@ drf_status forward(drf_denoiser* d, const float* x, const SlotMap& map, const fl
     }
     const double ln_bytes = (double)M * D * (4.0 + (f32 ? 4.0 : 2.0));
     const size_t act = f32 ? 4 : 2;
+    // bf16 path: the gated branch outputs (attention projection, MLP) are written as bf16 and added to
+    // the fp32 residual stream by the LayerNorm launch that reads it next, instead of a read-modify-
+    // write of the stream in the GEMM epilogue (where it cannot overlap the MFMA loop).  `pending`
+    // is the branch output not yet added.  The last block's MLP updates the stream directly.
+    const bf16_t* pending = nullptr;
+    auto ln = [&](const float* shift, const float* scale, int mod_ld) -> drf_status {
+        ProfScope ps(d, st, DRF_PROF_ELEMWISE, ln_bytes + (pending ? (double)M * D * 6.0 : 0.0));
+        const drf_status r = launch_ln_modulate(d->resid, pending, shift, scale, mod_ld, dm.T, M, D, d->hbuf, f32, st);
+        pending = nullptr;
+        return r;
+    };
     for (int l = 0; l < n_blocks; ++l) {
         const BlockW& b = d->blk[l];
         const float* mrow = mod + (size_t)l * 6 * D;        // shift1 | scale1 | gate1 | shift2 | scale2 | gate2
-        {
-            ProfScope ps(d, st, DRF_PROF_ELEMWISE, ln_bytes);
-            if ((rc = launch_ln_modulate(d->resid, mrow, mrow + D, nm, dm.T, M, D, d->hbuf, f32, st)) != DRF_OK) return rc;
-        }
+        if ((rc = ln(mrow, mrow + D, nm)) != DRF_OK) return rc;
         // bf16: q | k | v are stored head-major ([slot][head][token][d] planes) so that attention reads
         // whole contiguous tiles; fp32: packed rows
         if ((rc = gemm(d, d->hbuf, b.qkv, M, f32 ? epi_store(d->qkv, 3 * D, true) : epi_heads(d->qkv, M, dm), st)) != DRF_OK) return rc;
@@ -311,13 +329,15 @@ drf_status forward(drf_denoiser* d, const float* x, const SlotMap& map, const fl
             ProfScope ps(d, st, DRF_PROF_ATTN, 4.0 * slots * dm.heads * (double)dm.T * dm.T * dm.d);
             if ((rc = f32 ? launch_attn_f32(aa, st) : launch_attn_bf16(aa, st)) != DRF_OK) return rc;
         }
-        if ((rc = gemm(d, d->hbuf, b.proj, M, epi_resid(d->resid, D, mrow + 2 * D, nm, dm.T), st)) != DRF_OK) return rc;
+        if (f32) {
+            if ((rc = gemm(d, d->hbuf, b.proj, M, epi_resid(d->resid, D, mrow + 2 * D, nm, dm.T), st)) != DRF_OK) return rc;
+        } else {
+            if ((rc = gemm(d, d->hbuf, b.proj, M, epi_gated(d->ybuf, D, mrow + 2 * D, nm, dm.T), st)) != DRF_OK) return rc;
+            pending = (const bf16_t*)d->ybuf;
+        }
         if (d->cfg.cond == DRF_COND_TEXT) {
             const int ctx_rows = map.cond_mod ? map.cond_mod : slots;
-            {
-                ProfScope ps(d, st, DRF_PROF_ELEMWISE, ln_bytes);
-                if ((rc = launch_ln_modulate(d->resid, nullptr, nullptr, 0, dm.T, M, D, d->hbuf, f32, st)) != DRF_OK) return rc;
-            }
+            if ((rc = ln(nullptr, nullptr, 0)) != DRF_OK) return rc;
             if ((rc = gemm(d, d->hbuf, b.xq, M, epi_store(d->qkv, D, f32), st)) != DRF_OK) return rc;
             const char* kv = (const char*)d->xkv + (size_t)l * ctx_rows * d->cfg.ctx_len * 2 * D * act;
             AttnArgs aa{};
@@ -331,12 +351,14 @@ drf_status forward(drf_denoiser* d, const float* x, const SlotMap& map, const fl
             }
             if ((rc = gemm(d, d->hbuf, b.xo, M, epi_resid(d->resid, D, nullptr, 0, dm.T), st)) != DRF_OK) return rc;
         }
-        {
-            ProfScope ps(d, st, DRF_PROF_ELEMWISE, ln_bytes);
-            if ((rc = launch_ln_modulate(d->resid, mrow + 3 * D, mrow + 4 * D, nm, dm.T, M, D, d->hbuf, f32, st)) != DRF_OK) return rc;
-        }
+        if ((rc = ln(mrow + 3 * D, mrow + 4 * D, nm)) != DRF_OK) return rc;
         if ((rc = gemm(d, d->hbuf, b.fc1, M, epi_store(d->mid, dm.R * D, f32, true), st)) != DRF_OK) return rc;
-        if ((rc = gemm(d, d->mid, b.fc2, M, epi_resid(d->resid, D, mrow + 5 * D, nm, dm.T), st)) != DRF_OK) return rc;
+        if (f32 || l == n_blocks - 1) {
+            if ((rc = gemm(d, d->mid, b.fc2, M, epi_resid(d->resid, D, mrow + 5 * D, nm, dm.T), st)) != DRF_OK) return rc;
+        } else {
+            if ((rc = gemm(d, d->mid, b.fc2, M, epi_gated(d->ybuf, D, mrow + 5 * D, nm, dm.T), st)) != DRF_OK) return rc;
+            pending = (const bf16_t*)d->ybuf;
+        }
     }
     if (resid_out) {
         DRF_HIP(hipMemcpyAsync(resid_out, d->resid, (size_t)M * D * 4, hipMemcpyDeviceToDevice, st));

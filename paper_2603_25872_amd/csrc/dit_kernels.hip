@@ -161,21 +161,28 @@ template <> struct Pair<float> { typedef float2 type; };
 template <> struct Pair<bf16_t> { typedef bf16_t type __attribute__((ext_vector_type(2))); };
 
 template <int PER, typename OutT>
-__global__ void __launch_bounds__(256) ln_modulate_kernel(const float* __restrict__ resid, const float* __restrict__ shift,
+__global__ void __launch_bounds__(256) ln_modulate_kernel(float* __restrict__ resid, const bf16_t* __restrict__ add,
+                                                          const float* __restrict__ shift,
                                                           const float* __restrict__ scale, int mod_ld, int rows_per_slot,
                                                           int M, int D, OutT* __restrict__ out)
 {
     typedef typename Pair<OutT>::type out2;
+    typedef bf16_t bf16x2 __attribute__((ext_vector_type(2)));
     const int lane = threadIdx.x & 63, row = blockIdx.x * (blockDim.x >> 6) + (threadIdx.x >> 6);
     if (row >= M) return;
     const int D2 = D >> 1;
-    const float2* xr = reinterpret_cast<const float2*>(resid + (size_t)row * D);
+    float2* xr = reinterpret_cast<float2*>(resid + (size_t)row * D);
     float2 v[PER];
     float sum = 0.f;
 #pragma unroll
     for (int i = 0; i < PER; ++i) {
         const int j = i * kWave + lane;
         v[i] = j < D2 ? xr[j] : make_float2(0.f, 0.f);
+        if (add && j < D2) {                   // pending branch output: resid += add, written back
+            const bf16x2 a2 = reinterpret_cast<const bf16x2*>(add + (size_t)row * D)[j];
+            v[i].x += (float)a2.x; v[i].y += (float)a2.y;
+            xr[j] = v[i];
+        }
         sum += v[i].x + v[i].y;
     }
     const float mean = wave_sum(sum) / (float)D;
@@ -216,20 +223,31 @@ __device__ inline float half_wave_sum(float v)
     for (int o = 16; o >= 1; o >>= 1) v += __shfl_xor(v, o, 64);
     return v;
 }
-template <int PER4, typename OutT>
-__global__ void __launch_bounds__(256) ln_modulate4_kernel(const float* __restrict__ resid, const float* __restrict__ shift,
+template <int PER4, typename OutT, bool ADD>
+__global__ void __launch_bounds__(256) ln_modulate4_kernel(float* __restrict__ resid, const bf16_t* __restrict__ add,
+                                                           const float* __restrict__ shift,
                                                            const float* __restrict__ scale, int mod_ld, int rows_per_slot,
                                                            int M, OutT* __restrict__ out)
 {
     constexpr int D = PER4 * 128;
+    typedef bf16_t bf16x4 __attribute__((ext_vector_type(4)));
     const int l32 = threadIdx.x & 31, row = blockIdx.x * (blockDim.x >> 5) + (threadIdx.x >> 5);
     if (row >= M) return;                       // M is even here or the spare half wave idles: no block barrier below
-    const float4* xr = reinterpret_cast<const float4*>(resid + (size_t)row * D);
+    float4* xr = reinterpret_cast<float4*>(resid + (size_t)row * D);
     float4 v[PER4];
-    float sum = 0.f;
+    bf16x4 a4[ADD ? PER4 : 1];
 #pragma unroll
     for (int i = 0; i < PER4; ++i) {
         v[i] = xr[i * 32 + l32];
+        if constexpr (ADD) a4[i] = reinterpret_cast<const bf16x4*>(add + (size_t)row * D)[i * 32 + l32];
+    }
+    float sum = 0.f;
+#pragma unroll
+    for (int i = 0; i < PER4; ++i) {
+        if constexpr (ADD) {                    // pending branch output: resid += add, written back
+            v[i].x += (float)a4[i][0]; v[i].y += (float)a4[i][1]; v[i].z += (float)a4[i][2]; v[i].w += (float)a4[i][3];
+            xr[i * 32 + l32] = v[i];
+        }
         sum += (v[i].x + v[i].y) + (v[i].z + v[i].w);
     }
     const float mean = half_wave_sum(sum) * (1.f / (float)D);
@@ -255,7 +273,6 @@ __global__ void __launch_bounds__(256) ln_modulate4_kernel(const float* __restri
         if constexpr (sizeof(OutT) == 4) {
             reinterpret_cast<float4*>(out + (size_t)row * D)[j] = make_float4(y0, y1, y2, y3);
         } else {
-            typedef bf16_t bf16x4 __attribute__((ext_vector_type(4)));
             const bf16x4 o = { (bf16_t)y0, (bf16_t)y1, (bf16_t)y2, (bf16_t)y3 };
             reinterpret_cast<bf16x4*>(out + (size_t)row * D)[j] = o;
         }
@@ -376,55 +393,60 @@ drf_status launch_patch_embed(const float* x, const SlotMap& map, const float* w
 }
 
 template <int PER>
-static void launch_ln_inst(const float* resid, const float* shift, const float* scale, int mod_ld, int rows_per_slot, int M,
+static void launch_ln_inst(float* resid, const bf16_t* add, const float* shift, const float* scale, int mod_ld, int rows_per_slot, int M,
                            int D, void* out, int out_f32, hipStream_t st)
 {
     const dim3 grid((M + 3) / 4), block(256);
     if (out_f32)
-        hipLaunchKernelGGL((ln_modulate_kernel<PER, float>), grid, block, 0, st, resid, shift, scale, mod_ld, rows_per_slot, M,
+        hipLaunchKernelGGL((ln_modulate_kernel<PER, float>), grid, block, 0, st, resid, add, shift, scale, mod_ld, rows_per_slot, M,
                            D, (float*)out);
     else
-        hipLaunchKernelGGL((ln_modulate_kernel<PER, bf16_t>), grid, block, 0, st, resid, shift, scale, mod_ld, rows_per_slot,
+        hipLaunchKernelGGL((ln_modulate_kernel<PER, bf16_t>), grid, block, 0, st, resid, add, shift, scale, mod_ld, rows_per_slot,
                            M, D, (bf16_t*)out);
 }
 
 template <int PER4>
-void launch_ln4_inst(const float* resid, const float* shift, const float* scale, int mod_ld, int rows_per_slot, int M,
-                     void* out, int out_f32, hipStream_t st)
+void launch_ln4_inst(float* resid, const bf16_t* add, const float* shift, const float* scale, int mod_ld, int rows_per_slot,
+                     int M, void* out, int out_f32, hipStream_t st)
 {
     const dim3 grid((M + 7) / 8), block(256);
     if (out_f32)
-        hipLaunchKernelGGL((ln_modulate4_kernel<PER4, float>), grid, block, 0, st, resid, shift, scale, mod_ld, rows_per_slot, M,
-                           (float*)out);
+        hipLaunchKernelGGL((ln_modulate4_kernel<PER4, float, false>), grid, block, 0, st, resid, add, shift, scale, mod_ld,
+                           rows_per_slot, M, (float*)out);
+    else if (add)
+        hipLaunchKernelGGL((ln_modulate4_kernel<PER4, bf16_t, true>), grid, block, 0, st, resid, add, shift, scale, mod_ld,
+                           rows_per_slot, M, (bf16_t*)out);
     else
-        hipLaunchKernelGGL((ln_modulate4_kernel<PER4, bf16_t>), grid, block, 0, st, resid, shift, scale, mod_ld, rows_per_slot,
-                           M, (bf16_t*)out);
+        hipLaunchKernelGGL((ln_modulate4_kernel<PER4, bf16_t, false>), grid, block, 0, st, resid, add, shift, scale, mod_ld,
+                           rows_per_slot, M, (bf16_t*)out);
 }
 
-drf_status launch_ln_modulate(const float* resid, const float* shift, const float* scale, int mod_ld, int rows_per_slot,
-                              int M, int D, void* out, int out_f32, hipStream_t st)
+drf_status launch_ln_modulate(float* resid, const bf16_t* add, const float* shift, const float* scale, int mod_ld,
+                              int rows_per_slot, int M, int D, void* out, int out_f32, hipStream_t st)
 {
     if (M == 0) return DRF_OK;
+    if (add && out_f32) DRF_FAIL(DRF_ESHAPE, "the pending-branch add is a bf16-path feature");
     if (D > 2048 || D % 2 != 0 || mod_ld % 2 != 0) DRF_FAIL(DRF_ESHAPE, "LayerNorm kernel needs even hidden <= 2048 (got %d)", D);
     const bool al16 = mod_ld % 4 == 0 && ((reinterpret_cast<uintptr_t>(resid) | reinterpret_cast<uintptr_t>(out) |
-                                           reinterpret_cast<uintptr_t>(shift) | reinterpret_cast<uintptr_t>(scale)) & 15u) == 0;
+                                           reinterpret_cast<uintptr_t>(shift) | reinterpret_cast<uintptr_t>(scale) |
+                                           reinterpret_cast<uintptr_t>(add)) & 15u) == 0;
     if (al16 && (D == 1152 || D == 384 || D == 768 || D == 1024 || D == 128)) {
         switch (D / 128) {
-        case 1: launch_ln4_inst<1>(resid, shift, scale, mod_ld, rows_per_slot, M, out, out_f32, st); break;
-        case 3: launch_ln4_inst<3>(resid, shift, scale, mod_ld, rows_per_slot, M, out, out_f32, st); break;
-        case 6: launch_ln4_inst<6>(resid, shift, scale, mod_ld, rows_per_slot, M, out, out_f32, st); break;
-        case 8: launch_ln4_inst<8>(resid, shift, scale, mod_ld, rows_per_slot, M, out, out_f32, st); break;
-        default: launch_ln4_inst<9>(resid, shift, scale, mod_ld, rows_per_slot, M, out, out_f32, st); break;
+        case 1: launch_ln4_inst<1>(resid, add, shift, scale, mod_ld, rows_per_slot, M, out, out_f32, st); break;
+        case 3: launch_ln4_inst<3>(resid, add, shift, scale, mod_ld, rows_per_slot, M, out, out_f32, st); break;
+        case 6: launch_ln4_inst<6>(resid, add, shift, scale, mod_ld, rows_per_slot, M, out, out_f32, st); break;
+        case 8: launch_ln4_inst<8>(resid, add, shift, scale, mod_ld, rows_per_slot, M, out, out_f32, st); break;
+        default: launch_ln4_inst<9>(resid, add, shift, scale, mod_ld, rows_per_slot, M, out, out_f32, st); break;
         }
         DRF_HIP(hipGetLastError());
         return DRF_OK;
     }
     const int per = (D / 2 + kWave - 1) / kWave;      // column pairs per lane
-    if (per <= 1) launch_ln_inst<1>(resid, shift, scale, mod_ld, rows_per_slot, M, D, out, out_f32, st);
-    else if (per <= 3) launch_ln_inst<3>(resid, shift, scale, mod_ld, rows_per_slot, M, D, out, out_f32, st);
-    else if (per <= 5) launch_ln_inst<5>(resid, shift, scale, mod_ld, rows_per_slot, M, D, out, out_f32, st);
-    else if (per <= 9) launch_ln_inst<9>(resid, shift, scale, mod_ld, rows_per_slot, M, D, out, out_f32, st);
-    else launch_ln_inst<16>(resid, shift, scale, mod_ld, rows_per_slot, M, D, out, out_f32, st);
+    if (per <= 1) launch_ln_inst<1>(resid, add, shift, scale, mod_ld, rows_per_slot, M, D, out, out_f32, st);
+    else if (per <= 3) launch_ln_inst<3>(resid, add, shift, scale, mod_ld, rows_per_slot, M, D, out, out_f32, st);
+    else if (per <= 5) launch_ln_inst<5>(resid, add, shift, scale, mod_ld, rows_per_slot, M, D, out, out_f32, st);
+    else if (per <= 9) launch_ln_inst<9>(resid, add, shift, scale, mod_ld, rows_per_slot, M, D, out, out_f32, st);
+    else launch_ln_inst<16>(resid, add, shift, scale, mod_ld, rows_per_slot, M, D, out, out_f32, st);
     DRF_HIP(hipGetLastError());
     return DRF_OK;
 }

@@ -56,6 +56,10 @@ __device__ inline void epilogue4(const Epilogue& e, int m, int n, float v0, floa
         return;
     }
     if (e.mode == EPI_STORE_GELU) { v0 = gelu_tanh(v0); v1 = gelu_tanh(v1); v2 = gelu_tanh(v2); v3 = gelu_tanh(v3); }
+    if (e.mode == EPI_STORE_GATED) {
+        const float4 g = *reinterpret_cast<const float4*>(e.gate + (size_t)fast_div(m, e.rps_magic, e.rps_shift) * e.gate_ld + n);
+        v0 *= g.x; v1 *= g.y; v2 *= g.z; v3 *= g.w;
+    }
     if (e.out_f32) {
         *reinterpret_cast<float4*>((float*)e.out + (size_t)m * e.ldo + n) = make_float4(v0, v1, v2, v3);
     } else {
@@ -471,10 +475,21 @@ gemm_bf16_xl_kernel(const bf16_t* __restrict__ A, const bf16_t* __restrict__ W, 
                 for (int jj = 0; jj < RPP / 16; ++jj) {
                     const int j = j0 + jj;
                     if (j < MI) {
+                        // EPI_STORE_GATED: the gate row of this lane's output row (rows past M use the last one)
+                        const float* grow = nullptr;
+                        if constexpr (MODE == EPI_STORE_GATED) {
+                            const int mr = mw + j * 16 + l16;
+                            grow = e.gate + (size_t)fast_div(mr < M ? mr : M - 1, e.rps_magic, e.rps_shift) * e.gate_ld;
+                        }
 #pragma unroll
                         for (int i = 0; i < NI; ++i) {
                             float v0 = acc[i][j][0] + bb[i].x, v1 = acc[i][j][1] + bb[i].y, v2 = acc[i][j][2] + bb[i].z, v3 = acc[i][j][3] + bb[i].w;
                             if (MODE == EPI_STORE_GELU) { v0 = gelu_tanh(v0); v1 = gelu_tanh(v1); v2 = gelu_tanh(v2); v3 = gelu_tanh(v3); }
+                            if constexpr (MODE == EPI_STORE_GATED) {
+                                const int ng = nw + i * 16 + 4 * quarter;
+                                const float4 g = *reinterpret_cast<const float4*>(grow + (ng < N ? ng : 0));
+                                v0 *= g.x; v1 *= g.y; v2 *= g.z; v3 *= g.w;
+                            }
                             bf16x4 o = { (bf16_t)v0, (bf16_t)v1, (bf16_t)v2, (bf16_t)v3 };
                             *reinterpret_cast<bf16x4*>(wbuf + (jj * 16 + l16) * ROWB + (i * 16 + 4 * quarter) * 2) = o;
                         }
@@ -496,6 +511,7 @@ gemm_bf16_xl_kernel(const bf16_t* __restrict__ A, const bf16_t* __restrict__ W, 
         };
         if (e.mode == EPI_STORE_GELU) run(std::integral_constant<int, EPI_STORE_GELU>{});
         else if (e.mode == EPI_STORE_HEADS) run(std::integral_constant<int, EPI_STORE_HEADS>{});
+        else if (e.mode == EPI_STORE_GATED) run(std::integral_constant<int, EPI_STORE_GATED>{});
         else run(std::integral_constant<int, EPI_STORE>{});
     }
 }
@@ -579,6 +595,7 @@ drf_status launch_gemm_bf16(const bf16_t* A, const bf16_t* W, int M, int N, int 
     if (K % 64 != 0 || N % 4 != 0 || e.ldo % 4 != 0) DRF_FAIL(DRF_ESHAPE, "bf16 GEMM needs K %% 64 == 0 and N %% 4 == 0 (M=%d N=%d K=%d)", M, N, K);
     if (e.mode == EPI_STORE_HEADS && (e.out_f32 || e.hd % 8 != 0 || N % e.hid != 0))
         DRF_FAIL(DRF_ESHAPE, "head-major store needs bf16 output and head width %% 8 == 0");
+    if (e.mode == EPI_STORE_GATED && (e.out_f32 || !e.gate)) DRF_FAIL(DRF_ESHAPE, "gated store needs bf16 output and a gate");
     if ((size_t)M * K >= ((size_t)1 << 31) || (size_t)N * K >= ((size_t)1 << 31))
         DRF_FAIL(DRF_ESHAPE, "bf16 GEMM operand exceeds 2^31 elements");
     int v = g_gemm_variant;
