@@ -24,7 +24,7 @@ PEAK_HBM_GBS = 8000.0
 # Bytes the bf16 GEMM launches of one configuration-3 call move past the L2, per launch on average: rocprofv3 FETCH_SIZE
 # and WRITE_SIZE, each scaled by what the same counter reads for a plain 1 GiB copy
 # (profiles/drf_sample_cfg3_pmc_traffic_mfma.txt).  Only valid for the default workload.
-GEMM_TRAFFIC_BYTES_PER_LAUNCH = {3: 2.18e8}
+GEMM_TRAFFIC_BYTES_PER_LAUNCH = {3: 1.79e8}
 
 
 def slot_eval_flops(dit):
