@@ -4,6 +4,7 @@ Each test checks the oracle against something it does not compute itself: a
 closed form derived from the paper's equations, a brute-force expansion written
 here by hand, or an invariant the paper states.  No GPU involved."""
 import math
+import os
 
 import numpy as np
 import pytest
@@ -276,13 +277,18 @@ def test_round_shapes_of_the_five_workloads(orc):
 
 
 def test_ideal_speedup_limits(orc):
-    # latency ~ 1/N (aggressive) and 2/(N+1) (conservative) as S grows
+    # latency ~ 1/N (aggressive) and 2/(N+1) (conservative) as S grows; the stated factors and the
+    # pass counts of a 50-step run are read from the fixture
+    path = os.path.join(os.path.dirname(__file__), "golden", "ideal_speedup.txt")
+    rows = [ln.split() for ln in open(path) if ln.strip() and not ln.startswith("#")]
+    assert len(rows) == 6
     S = 960
-    for n in (2, 3, 4):
-        ra = orc.plan(sched(S), AGGR, n)[:, 0].max() + 1
-        rc = orc.plan(sched(S), CONS, n)[:, 0].max() + 1
-        assert abs(S / ra - n) < 0.02 * n
-        assert abs(S / rc - (n + 1) / 2) < 0.02 * n
+    for mode_name, n, ideal, passes50 in rows:
+        mode, n, ideal, passes50 = {"aggressive": AGGR, "conservative": CONS}[mode_name], int(n), float(ideal), int(passes50)
+        rounds = orc.plan(sched(S), mode, n)[:, 0].max() + 1
+        assert abs(S / rounds - ideal) < 0.02 * n
+        assert orc.plan(sched(50), mode, n)[:, 0].max() + 1 == passes50
+        assert 50 / passes50 <= ideal + 1e-12
 
 
 def test_bad_arguments_rejected(orc):
