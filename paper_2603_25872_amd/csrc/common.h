@@ -110,6 +110,11 @@ struct Epilogue {
     //   out[which * plane + ((slot * heads + head) * rows_per_slot + t) * hd + dd]     (q | k | v planes, head-major)
     int hid, hd, heads; size_t plane;
     uint32_t hid_magic, hd_magic; int hid_shift, hd_shift;
+    // Optional (bf16 wide-tile kernel only): the last 256 workgroups of the launch (the ones that run in
+    // its final round) each load one word of their share of the warm_lines 128-byte lines at `warm`,
+    // typically the weights of the GEMM that runs next, so that those are already on the near side of
+    // HBM when that GEMM asks for them.  Values are not used.
+    const void* warm; uint32_t warm_lines;
 };
 // Division constants for floor(n / d), 0 <= n < 2^31 (see fast_div in gemm.hip).
 void make_fast_div(int d, uint32_t* magic, int* shift);

@@ -238,6 +238,13 @@ Epilogue epi_resid(float* resid, int ldo, const float* gate, int gate_ld, int ro
     return e;
 }
 
+// Asks a bf16 GEMM launch to warm the caches with the weights of a later one (see Epilogue::warm).
+Epilogue with_warm(Epilogue e, const LinearW* next)
+{
+    if (next && next->w16) { e.warm = next->w16; e.warm_lines = (uint32_t)(((size_t)next->N * next->K * 2) / 128); }
+    return e;
+}
+
 // K/V of the text context for every block: xkv[l][row][ctx][2D] = Linear(ctx[row]).
 drf_status compute_ctx_kv(drf_denoiser* d, const float* ctx, int rows, hipStream_t st)
 {
@@ -299,7 +306,12 @@ drf_status forward(drf_denoiser* d, const float* x, const SlotMap& map, const fl
     // the fp32 residual stream by the LayerNorm launch that reads it next, instead of a read-modify-
     // write of the stream in the GEMM epilogue (where it cannot overlap the MFMA loop).  `pending`
     // is the branch output not yet added.  The last block's MLP updates the stream directly.
+    // Every pass streams all block weights from HBM (they do not fit the caches between passes), and a
+    // GEMM whose k-loop waits on first-touch weight lines runs measurably slower than the same GEMM with
+    // warm weights.  So each bf16 GEMM of the block chain (qkv -> proj -> fc1 -> fc2 -> next block's
+    // qkv) touches the weights of its successor while its own last round of tiles starts.
     const bf16_t* pending = nullptr;
+    const bool text = d->cfg.cond == DRF_COND_TEXT;
     auto ln = [&](const float* shift, const float* scale, int mod_ld) -> drf_status {
         ProfScope ps(d, st, DRF_PROF_ELEMWISE, ln_bytes + (pending ? (double)M * D * 6.0 : 0.0));
         const drf_status r = launch_ln_modulate(d->resid, pending, shift, scale, mod_ld, dm.T, M, D, d->hbuf, f32, st);
@@ -312,7 +324,7 @@ drf_status forward(drf_denoiser* d, const float* x, const SlotMap& map, const fl
         if ((rc = ln(mrow, mrow + D, nm)) != DRF_OK) return rc;
         // bf16: q | k | v are stored head-major ([slot][head][token][d] planes) so that attention reads
         // whole contiguous tiles; fp32: packed rows
-        if ((rc = gemm(d, d->hbuf, b.qkv, M, f32 ? epi_store(d->qkv, 3 * D, true) : epi_heads(d->qkv, M, dm), st)) != DRF_OK) return rc;
+        if ((rc = gemm(d, d->hbuf, b.qkv, M, f32 ? epi_store(d->qkv, 3 * D, true) : with_warm(epi_heads(d->qkv, M, dm), &b.proj), st)) != DRF_OK) return rc;
         {
             AttnArgs aa{};
             aa.q = d->qkv; aa.out = d->hbuf; aa.ldo = D; aa.Nq = dm.T; aa.Nk = dm.T; aa.heads = dm.heads; aa.d = dm.d;
@@ -332,7 +344,7 @@ drf_status forward(drf_denoiser* d, const float* x, const SlotMap& map, const fl
         if (f32) {
             if ((rc = gemm(d, d->hbuf, b.proj, M, epi_resid(d->resid, D, mrow + 2 * D, nm, dm.T), st)) != DRF_OK) return rc;
         } else {
-            if ((rc = gemm(d, d->hbuf, b.proj, M, epi_gated(d->ybuf, D, mrow + 2 * D, nm, dm.T), st)) != DRF_OK) return rc;
+            if ((rc = gemm(d, d->hbuf, b.proj, M, with_warm(epi_gated(d->ybuf, D, mrow + 2 * D, nm, dm.T), text ? nullptr : &b.fc1), st)) != DRF_OK) return rc;
             pending = (const bf16_t*)d->ybuf;
         }
         if (d->cfg.cond == DRF_COND_TEXT) {
@@ -352,11 +364,11 @@ drf_status forward(drf_denoiser* d, const float* x, const SlotMap& map, const fl
             if ((rc = gemm(d, d->hbuf, b.xo, M, epi_resid(d->resid, D, nullptr, 0, dm.T), st)) != DRF_OK) return rc;
         }
         if ((rc = ln(mrow + 3 * D, mrow + 4 * D, nm)) != DRF_OK) return rc;
-        if ((rc = gemm(d, d->hbuf, b.fc1, M, epi_store(d->mid, dm.R * D, f32, true), st)) != DRF_OK) return rc;
+        if ((rc = gemm(d, d->hbuf, b.fc1, M, with_warm(epi_store(d->mid, dm.R * D, f32, true), f32 ? nullptr : &b.fc2), st)) != DRF_OK) return rc;
         if (f32 || l == n_blocks - 1) {
             if ((rc = gemm(d, d->mid, b.fc2, M, epi_resid(d->resid, D, mrow + 5 * D, nm, dm.T), st)) != DRF_OK) return rc;
         } else {
-            if ((rc = gemm(d, d->mid, b.fc2, M, epi_gated(d->ybuf, D, mrow + 5 * D, nm, dm.T), st)) != DRF_OK) return rc;
+            if ((rc = gemm(d, d->mid, b.fc2, M, with_warm(epi_gated(d->ybuf, D, mrow + 5 * D, nm, dm.T), &d->blk[l + 1].qkv), st)) != DRF_OK) return rc;
             pending = (const bf16_t*)d->ybuf;
         }
     }

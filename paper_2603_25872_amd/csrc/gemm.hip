@@ -245,6 +245,20 @@ gemm_bf16_xl_kernel(const bf16_t* __restrict__ A, const bf16_t* __restrict__ W, 
     const int wk = wave / NWT, wl = wave % NWT, wm = wl % WM, wn = wl / WM;
     const int l16 = lane & 15, quarter = lane >> 4;
 
+    // Cache warm-up for a later launch (see Epilogue::warm): the lines are dealt over the workgroups of
+    // the last round, a thread loads one word per line; the values are only consumed by an empty asm
+    // after the first barrier, so the loads complete together with the first operand tiles.
+    unsigned warm_val = 0;
+    if (e.warm_lines) {
+        const uint32_t first = nb > 256 ? (uint32_t)nb - 256u : 0u, cnt = (uint32_t)nb - first;
+        const uint32_t per = (e.warm_lines + cnt - 1u) / cnt;
+        if ((uint32_t)b >= first)
+            for (uint32_t t = (uint32_t)tid; t < per; t += NW * 64) {
+                const uint32_t line = ((uint32_t)b - first) * per + t;
+                if (line < e.warm_lines) warm_val ^= reinterpret_cast<const unsigned*>(e.warm)[(size_t)line * 32];
+            }
+    }
+
     // DMA: the A rows and W rows of a k-tile form one row space [0, BM + BN), and a stage holds WK
     // k-tiles one after the other.  A wave-wide instruction covers RPI rows (never straddling the
     // A/W boundary).  Every wave issues LPT instructions; when SEG is not a multiple of the wave
@@ -326,6 +340,7 @@ gemm_bf16_xl_kernel(const bf16_t* __restrict__ A, const bf16_t* __restrict__ W, 
         if (t < nk) issue(t, t);
     if (NS > 2 && nk >= NS - 1) wait_vmcnt<LPT * (NS - 2)>(); else wait_vmcnt<0>();
     asm volatile("s_barrier" ::: "memory");
+    asm volatile("" ::"v"(warm_val));
     if (NS - 1 < nk) issue(NS - 1, NS - 1);
     static_for<0, D>([&](auto pc) { fetch(pc, a_addr, w_addr); });
     int cs = 0;                                     // stage of tile kt
