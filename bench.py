@@ -24,7 +24,7 @@ PEAK_HBM_GBS = 8000.0
 # Bytes the bf16 GEMM launches of one configuration-3 call move past the L2, per launch on average: rocprofv3 FETCH_SIZE
 # and WRITE_SIZE, each scaled by what the same counter reads for a plain 1 GiB copy
 # (profiles/drf_sample_cfg3_pmc_traffic_mfma.txt).  Only valid for the default workload.
-GEMM_TRAFFIC_BYTES_PER_LAUNCH = {3: 1.79e8}
+GEMM_TRAFFIC_BYTES_PER_LAUNCH = {3: 1.873e8}
 
 
 def slot_eval_flops(dit):
@@ -53,6 +53,9 @@ def main():
     ap.add_argument("--seed", type=int, default=1, help="seed of the library's noise stream (stochastic samplers)")
     ap.add_argument("--no-cpu-baseline", action="store_true")
     ap.add_argument("--no-roofline", action="store_true")
+    ap.add_argument("--copy-calibration", action="store_true",
+                    help="only run three plain 1 GiB device-to-device copies: the kernel of known size against "
+                         "which the FETCH_SIZE / WRITE_SIZE counters of a profiler run are scaled")
     args = ap.parse_args()
     if args.gpus != 1:
         sys.exit("bench.py: this build runs on one GPU; the paper's n devices are n batch-slot groups of a "
@@ -60,6 +63,14 @@ def main():
 
     import numpy as np
     import torch
+    if args.copy_calibration:
+        a = torch.empty(1 << 28, dtype=torch.float32, device="cuda").normal_()
+        b = torch.empty_like(a)
+        for _ in range(3):
+            b.copy_(a)
+        torch.cuda.synchronize()
+        print(json.dumps({"copy_calibration": {"bytes_read_per_copy": 1 << 30, "bytes_written_per_copy": 1 << 30, "copies": 3}}))
+        return
     from paper_2603_25872_amd import drf, inputs as I
 
     cfg = I.config(args.config)
