@@ -6,6 +6,7 @@
 #include <type_traits>
 
 #include "common.h"
+#include <cstdlib>
 
 namespace drf {
 
@@ -208,6 +209,11 @@ __global__ void __launch_bounds__(NW * 64) attn_bf16_kernel(const AttnArgs a, fl
             }
     };
 
+    // The Q fragments are settled here, before any chunk is in flight behind them: a first use inside
+    // the chunk loop would make the compiler wait for every outstanding load (vmcnt(0)) at each step,
+    // which would expose the loads of the chunk being prefetched.
+#pragma unroll
+    for (int ks = 0; ks < KS; ++ks) asm volatile("" : "+v"(qf[ks]));
     fetch(0);
     __syncthreads();                            // zero fill and ones row done
     stage(0);
@@ -318,6 +324,11 @@ drf_status launch_bf16_inst(const AttnArgs& a, float scale_log2, hipStream_t st)
     // rows go through one buffer of 128 rows refilled in place (measured slightly faster than staging
     // all 256 at once: the first MFMAs start after half the loads), longer sequences through two
     // buffers of 128 rows
+    if (const char* ev = getenv("DRF_ATTN")) {
+        const int c = atoi(ev);
+        if (c == 1) return launch_bf16_cfg<KS, DT, 8, 128, 2>(a, scale_log2, st);
+        if (c == 2) return launch_bf16_cfg<KS, DT, 8, 64, 2>(a, scale_log2, st);
+    }
     if (a.Nq > 128) {
         if (a.Nk <= 256) return launch_bf16_cfg<KS, DT, 8, 128, 1>(a, scale_log2, st);
         return launch_bf16_cfg<KS, DT, 8, 128, 2>(a, scale_log2, st);

@@ -154,9 +154,12 @@ drf_status launch_cond_embed(const CondArgs& a, hipStream_t st);
 drf_status launch_patch_embed(const float* x, const SlotMap& map, const float* w, const float* b, const float* pos,
                               const DitDims& dm, int slots, float* resid, hipStream_t st);
 // out = LN(resid) * (1 + scale) + shift (shift == NULL: plain LN); mod rows are per slot.
-// add != NULL (bf16 [M][D]): resid += add first, and the updated residual rows are written back.
-drf_status launch_ln_modulate(float* resid, const bf16_t* add, const float* shift, const float* scale, int mod_ld,
-                              int rows_per_slot, int M, int D, void* out, int out_f32, hipStream_t st);
+// add != NULL (bf16 [M][D], and add2 likewise if also != NULL): the rows normalised are x = (resid + add) + add2;
+// write_back stores x over resid, otherwise resid is left as it was and the caller passes the same `add`
+// again (with the next branch output as add2) to the launch that does write back.
+drf_status launch_ln_modulate(float* resid, const bf16_t* add, const bf16_t* add2, bool write_back, const float* shift,
+                              const float* scale, int mod_ld, int rows_per_slot, int M, int D, void* out, int out_f32,
+                              hipStream_t st);
 drf_status launch_final(const float* resid, const float* shift, const float* scale, int mod_ld, const float* w,
                         const float* b, const DitDims& dm, int slots, float* eps_out, hipStream_t st);
 drf_status launch_f32_to_bf16(const float* in, bf16_t* out, size_t n, hipStream_t st);

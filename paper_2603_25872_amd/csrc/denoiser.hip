@@ -45,7 +45,7 @@ struct drf_denoiser {
     // workspace
     int cap_slots = 0, cap_cond_rows = 0;
     float *resid = nullptr, *mod = nullptr, *cact32 = nullptr, *cscratch = nullptr;
-    void *hbuf = nullptr, *qkv = nullptr, *mid = nullptr, *ybuf = nullptr, *cact = nullptr;
+    void *hbuf = nullptr, *qkv = nullptr, *mid = nullptr, *ybuf = nullptr, *ybuf2 = nullptr, *cact = nullptr;
     // cross-attention K/V cache [L][rows][ctx_len][2D] and its staging
     void* xkv = nullptr; void* ctx_act = nullptr; int cap_ctx_rows = 0;
     // sampler buffers
@@ -149,7 +149,7 @@ drf_status ensure_workspace(drf_denoiser* d, int slots, hipStream_t st)
 {
     if (slots <= d->cap_slots) return DRF_OK;
     DRF_HIP(hipStreamSynchronize(st));
-    void* olds[] = { d->resid, d->hbuf, d->qkv, d->mid, d->ybuf };
+    void* olds[] = { d->resid, d->hbuf, d->qkv, d->mid, d->ybuf, d->ybuf2 };
     for (void* p : olds) dev_free(d, p);
     d->cap_slots = 0;
     const size_t M = (size_t)slots * d->dm.T, D = (size_t)d->dm.D, act = d->bf16 ? 2 : 4;
@@ -159,6 +159,7 @@ drf_status ensure_workspace(drf_denoiser* d, int slots, hipStream_t st)
     if ((rc = dev_alloc(d, &d->qkv, M * 3 * D * act)) != DRF_OK) return rc;
     if ((rc = dev_alloc(d, &d->mid, M * (size_t)d->dm.R * D * act)) != DRF_OK) return rc;
     if ((rc = dev_alloc(d, &d->ybuf, M * D * act)) != DRF_OK) return rc;
+    if ((rc = dev_alloc(d, &d->ybuf2, d->bf16 ? M * D * act : 0)) != DRF_OK) return rc;
     d->cap_slots = slots;
     return DRF_OK;
 }
@@ -303,25 +304,30 @@ drf_status forward(drf_denoiser* d, const float* x, const SlotMap& map, const fl
     const double ln_bytes = (double)M * D * (4.0 + (f32 ? 4.0 : 2.0));
     const size_t act = f32 ? 4 : 2;
     // bf16 path: the gated branch outputs (attention projection, MLP) are written as bf16 and added to
-    // the fp32 residual stream by the LayerNorm launch that reads it next, instead of a read-modify-
-    // write of the stream in the GEMM epilogue (where it cannot overlap the MFMA loop).  `pending`
-    // is the branch output not yet added.  The last block's MLP updates the stream directly.
+    // the fp32 residual stream by a LayerNorm launch that reads the stream anyway, instead of a
+    // read-modify-write of the stream in the GEMM epilogue (where it cannot overlap the MFMA loop).
+    // The stream is stored once per block, not twice: the LayerNorm before the MLP normalises
+    // resid + attention output without storing it, and the first LayerNorm of the next block adds both
+    // outputs, (resid + attention) + MLP in that order, and stores.  pend1 / pend2 are the outputs not
+    // yet in the stored stream.  The last block's MLP updates the stream directly, so the LayerNorm
+    // before it stores; so does the one before text cross-attention, whose projection does the same.
     // Every pass streams all block weights from HBM (they do not fit the caches between passes), and a
     // GEMM whose k-loop waits on first-touch weight lines runs measurably slower than the same GEMM with
     // warm weights.  So each bf16 GEMM of the block chain (qkv -> proj -> fc1 -> fc2 -> next block's
     // qkv) touches the weights of its successor while its own last round of tiles starts.
-    const bf16_t* pending = nullptr;
+    const bf16_t *pend1 = nullptr, *pend2 = nullptr;
     const bool text = d->cfg.cond == DRF_COND_TEXT;
-    auto ln = [&](const float* shift, const float* scale, int mod_ld) -> drf_status {
-        ProfScope ps(d, st, DRF_PROF_ELEMWISE, ln_bytes + (pending ? (double)M * D * 6.0 : 0.0));
-        const drf_status r = launch_ln_modulate(d->resid, pending, shift, scale, mod_ld, dm.T, M, D, d->hbuf, f32, st);
-        pending = nullptr;
+    auto ln = [&](const float* shift, const float* scale, int mod_ld, bool store) -> drf_status {
+        const int n_add = (pend1 ? 1 : 0) + (pend2 ? 1 : 0);
+        ProfScope ps(d, st, DRF_PROF_ELEMWISE, ln_bytes + (double)M * D * (2.0 * n_add + (n_add && store ? 4.0 : 0.0)));
+        const drf_status r = launch_ln_modulate(d->resid, pend1, pend2, store, shift, scale, mod_ld, dm.T, M, D, d->hbuf, f32, st);
+        if (store) pend1 = pend2 = nullptr;
         return r;
     };
     for (int l = 0; l < n_blocks; ++l) {
         const BlockW& b = d->blk[l];
         const float* mrow = mod + (size_t)l * 6 * D;        // shift1 | scale1 | gate1 | shift2 | scale2 | gate2
-        if ((rc = ln(mrow, mrow + D, nm)) != DRF_OK) return rc;
+        if ((rc = ln(mrow, mrow + D, nm, true)) != DRF_OK) return rc;
         // bf16: q | k | v are stored head-major ([slot][head][token][d] planes) so that attention reads
         // whole contiguous tiles; fp32: packed rows
         if ((rc = gemm(d, d->hbuf, b.qkv, M, f32 ? epi_store(d->qkv, 3 * D, true) : with_warm(epi_heads(d->qkv, M, dm), &b.proj), st)) != DRF_OK) return rc;
@@ -345,11 +351,11 @@ drf_status forward(drf_denoiser* d, const float* x, const SlotMap& map, const fl
             if ((rc = gemm(d, d->hbuf, b.proj, M, epi_resid(d->resid, D, mrow + 2 * D, nm, dm.T), st)) != DRF_OK) return rc;
         } else {
             if ((rc = gemm(d, d->hbuf, b.proj, M, with_warm(epi_gated(d->ybuf, D, mrow + 2 * D, nm, dm.T), text ? nullptr : &b.fc1), st)) != DRF_OK) return rc;
-            pending = (const bf16_t*)d->ybuf;
+            pend1 = (const bf16_t*)d->ybuf;
         }
         if (d->cfg.cond == DRF_COND_TEXT) {
             const int ctx_rows = map.cond_mod ? map.cond_mod : slots;
-            if ((rc = ln(nullptr, nullptr, 0)) != DRF_OK) return rc;
+            if ((rc = ln(nullptr, nullptr, 0, true)) != DRF_OK) return rc;
             if ((rc = gemm(d, d->hbuf, b.xq, M, epi_store(d->qkv, D, f32), st)) != DRF_OK) return rc;
             const char* kv = (const char*)d->xkv + (size_t)l * ctx_rows * d->cfg.ctx_len * 2 * D * act;
             AttnArgs aa{};
@@ -363,13 +369,16 @@ drf_status forward(drf_denoiser* d, const float* x, const SlotMap& map, const fl
             }
             if ((rc = gemm(d, d->hbuf, b.xo, M, epi_resid(d->resid, D, nullptr, 0, dm.T), st)) != DRF_OK) return rc;
         }
-        if ((rc = ln(mrow + 3 * D, mrow + 4 * D, nm)) != DRF_OK) return rc;
+        const bool last = l == n_blocks - 1;
+        if ((rc = ln(mrow + 3 * D, mrow + 4 * D, nm, f32 || last)) != DRF_OK) return rc;
         if ((rc = gemm(d, d->hbuf, b.fc1, M, with_warm(epi_store(d->mid, dm.R * D, f32, true), f32 ? nullptr : &b.fc2), st)) != DRF_OK) return rc;
-        if (f32 || l == n_blocks - 1) {
+        if (f32 || last) {
             if ((rc = gemm(d, d->mid, b.fc2, M, epi_resid(d->resid, D, mrow + 5 * D, nm, dm.T), st)) != DRF_OK) return rc;
         } else {
-            if ((rc = gemm(d, d->mid, b.fc2, M, with_warm(epi_gated(d->ybuf, D, mrow + 5 * D, nm, dm.T), &d->blk[l + 1].qkv), st)) != DRF_OK) return rc;
-            pending = (const bf16_t*)d->ybuf;
+            // the attention output may still be pending in ybuf: the MLP output goes to the second buffer
+            void* yo = pend1 ? d->ybuf2 : d->ybuf;
+            if ((rc = gemm(d, d->mid, b.fc2, M, with_warm(epi_gated(yo, D, mrow + 5 * D, nm, dm.T), &d->blk[l + 1].qkv), st)) != DRF_OK) return rc;
+            (pend1 ? pend2 : pend1) = (const bf16_t*)yo;
         }
     }
     if (resid_out) {

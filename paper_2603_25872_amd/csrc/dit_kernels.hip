@@ -162,6 +162,7 @@ template <> struct Pair<bf16_t> { typedef bf16_t type __attribute__((ext_vector_
 
 template <int PER, typename OutT>
 __global__ void __launch_bounds__(256) ln_modulate_kernel(float* __restrict__ resid, const bf16_t* __restrict__ add,
+                                                          const bf16_t* __restrict__ add2, int write_back,
                                                           const float* __restrict__ shift,
                                                           const float* __restrict__ scale, int mod_ld, int rows_per_slot,
                                                           int M, int D, OutT* __restrict__ out)
@@ -178,10 +179,14 @@ __global__ void __launch_bounds__(256) ln_modulate_kernel(float* __restrict__ re
     for (int i = 0; i < PER; ++i) {
         const int j = i * kWave + lane;
         v[i] = j < D2 ? xr[j] : make_float2(0.f, 0.f);
-        if (add && j < D2) {                   // pending branch output: resid += add, written back
+        if (add && j < D2) {                   // pending branch outputs: x = resid + add (+ add2), stored if asked
             const bf16x2 a2 = reinterpret_cast<const bf16x2*>(add + (size_t)row * D)[j];
             v[i].x += (float)a2.x; v[i].y += (float)a2.y;
-            xr[j] = v[i];
+            if (add2) {
+                const bf16x2 b2 = reinterpret_cast<const bf16x2*>(add2 + (size_t)row * D)[j];
+                v[i].x += (float)b2.x; v[i].y += (float)b2.y;
+            }
+            if (write_back) xr[j] = v[i];
         }
         sum += v[i].x + v[i].y;
     }
@@ -223,8 +228,9 @@ __device__ inline float half_wave_sum(float v)
     for (int o = 16; o >= 1; o >>= 1) v += __shfl_xor(v, o, 64);
     return v;
 }
-template <int PER4, typename OutT, bool ADD>
+template <int PER4, typename OutT, int ADD, bool WB>
 __global__ void __launch_bounds__(256) ln_modulate4_kernel(float* __restrict__ resid, const bf16_t* __restrict__ add,
+                                                           const bf16_t* __restrict__ add2,
                                                            const float* __restrict__ shift,
                                                            const float* __restrict__ scale, int mod_ld, int rows_per_slot,
                                                            int M, OutT* __restrict__ out)
@@ -235,18 +241,22 @@ __global__ void __launch_bounds__(256) ln_modulate4_kernel(float* __restrict__ r
     if (row >= M) return;                       // M is even here or the spare half wave idles: no block barrier below
     float4* xr = reinterpret_cast<float4*>(resid + (size_t)row * D);
     float4 v[PER4];
-    bf16x4 a4[ADD ? PER4 : 1];
+    bf16x4 a4[ADD >= 1 ? PER4 : 1], b4[ADD >= 2 ? PER4 : 1];
 #pragma unroll
     for (int i = 0; i < PER4; ++i) {
         v[i] = xr[i * 32 + l32];
-        if constexpr (ADD) a4[i] = reinterpret_cast<const bf16x4*>(add + (size_t)row * D)[i * 32 + l32];
+        if constexpr (ADD >= 1) a4[i] = reinterpret_cast<const bf16x4*>(add + (size_t)row * D)[i * 32 + l32];
+        if constexpr (ADD >= 2) b4[i] = reinterpret_cast<const bf16x4*>(add2 + (size_t)row * D)[i * 32 + l32];
     }
     float sum = 0.f;
 #pragma unroll
     for (int i = 0; i < PER4; ++i) {
-        if constexpr (ADD) {                    // pending branch output: resid += add, written back
+        if constexpr (ADD >= 1) {               // pending branch outputs: x = resid + add (+ add2), stored if WB
             v[i].x += (float)a4[i][0]; v[i].y += (float)a4[i][1]; v[i].z += (float)a4[i][2]; v[i].w += (float)a4[i][3];
-            xr[i * 32 + l32] = v[i];
+            if constexpr (ADD >= 2) {
+                v[i].x += (float)b4[i][0]; v[i].y += (float)b4[i][1]; v[i].z += (float)b4[i][2]; v[i].w += (float)b4[i][3];
+            }
+            if constexpr (WB) xr[i * 32 + l32] = v[i];
         }
         sum += (v[i].x + v[i].y) + (v[i].z + v[i].w);
     }
@@ -393,60 +403,64 @@ drf_status launch_patch_embed(const float* x, const SlotMap& map, const float* w
 }
 
 template <int PER>
-static void launch_ln_inst(float* resid, const bf16_t* add, const float* shift, const float* scale, int mod_ld, int rows_per_slot, int M,
-                           int D, void* out, int out_f32, hipStream_t st)
+static void launch_ln_inst(float* resid, const bf16_t* add, const bf16_t* add2, int write_back, const float* shift, const float* scale,
+                           int mod_ld, int rows_per_slot, int M, int D, void* out, int out_f32, hipStream_t st)
 {
     const dim3 grid((M + 3) / 4), block(256);
     if (out_f32)
-        hipLaunchKernelGGL((ln_modulate_kernel<PER, float>), grid, block, 0, st, resid, add, shift, scale, mod_ld, rows_per_slot, M,
-                           D, (float*)out);
+        hipLaunchKernelGGL((ln_modulate_kernel<PER, float>), grid, block, 0, st, resid, add, add2, write_back, shift, scale, mod_ld,
+                           rows_per_slot, M, D, (float*)out);
     else
-        hipLaunchKernelGGL((ln_modulate_kernel<PER, bf16_t>), grid, block, 0, st, resid, add, shift, scale, mod_ld, rows_per_slot,
-                           M, D, (bf16_t*)out);
+        hipLaunchKernelGGL((ln_modulate_kernel<PER, bf16_t>), grid, block, 0, st, resid, add, add2, write_back, shift, scale, mod_ld,
+                           rows_per_slot, M, D, (bf16_t*)out);
 }
 
 template <int PER4>
-void launch_ln4_inst(float* resid, const bf16_t* add, const float* shift, const float* scale, int mod_ld, int rows_per_slot,
-                     int M, void* out, int out_f32, hipStream_t st)
+void launch_ln4_inst(float* resid, const bf16_t* add, const bf16_t* add2, int write_back, const float* shift, const float* scale,
+                     int mod_ld, int rows_per_slot, int M, void* out, int out_f32, hipStream_t st)
 {
     const dim3 grid((M + 7) / 8), block(256);
-    if (out_f32)
-        hipLaunchKernelGGL((ln_modulate4_kernel<PER4, float, false>), grid, block, 0, st, resid, add, shift, scale, mod_ld,
-                           rows_per_slot, M, (float*)out);
-    else if (add)
-        hipLaunchKernelGGL((ln_modulate4_kernel<PER4, bf16_t, true>), grid, block, 0, st, resid, add, shift, scale, mod_ld,
-                           rows_per_slot, M, (bf16_t*)out);
-    else
-        hipLaunchKernelGGL((ln_modulate4_kernel<PER4, bf16_t, false>), grid, block, 0, st, resid, add, shift, scale, mod_ld,
-                           rows_per_slot, M, (bf16_t*)out);
+#define DRF_LN4(OUT, ADD, WB) \
+    hipLaunchKernelGGL((ln_modulate4_kernel<PER4, OUT, ADD, WB>), grid, block, 0, st, resid, add, add2, shift, scale, mod_ld, \
+                       rows_per_slot, M, (OUT*)out)
+    if (out_f32) DRF_LN4(float, 0, false);
+    else if (!add) DRF_LN4(bf16_t, 0, false);
+    else if (!add2 && write_back) DRF_LN4(bf16_t, 1, true);
+    else if (!add2) DRF_LN4(bf16_t, 1, false);
+    else if (write_back) DRF_LN4(bf16_t, 2, true);
+    else DRF_LN4(bf16_t, 2, false);
+#undef DRF_LN4
 }
 
-drf_status launch_ln_modulate(float* resid, const bf16_t* add, const float* shift, const float* scale, int mod_ld,
-                              int rows_per_slot, int M, int D, void* out, int out_f32, hipStream_t st)
+drf_status launch_ln_modulate(float* resid, const bf16_t* add, const bf16_t* add2, bool write_back, const float* shift,
+                              const float* scale, int mod_ld, int rows_per_slot, int M, int D, void* out, int out_f32,
+                              hipStream_t st)
 {
     if (M == 0) return DRF_OK;
     if (add && out_f32) DRF_FAIL(DRF_ESHAPE, "the pending-branch add is a bf16-path feature");
+    if (add2 && !add) DRF_FAIL(DRF_EINVAL, "a second pending branch output needs a first one");
     if (D > 2048 || D % 2 != 0 || mod_ld % 2 != 0) DRF_FAIL(DRF_ESHAPE, "LayerNorm kernel needs even hidden <= 2048 (got %d)", D);
+    const int wb = write_back ? 1 : 0;
     const bool al16 = mod_ld % 4 == 0 && ((reinterpret_cast<uintptr_t>(resid) | reinterpret_cast<uintptr_t>(out) |
                                            reinterpret_cast<uintptr_t>(shift) | reinterpret_cast<uintptr_t>(scale) |
-                                           reinterpret_cast<uintptr_t>(add)) & 15u) == 0;
+                                           reinterpret_cast<uintptr_t>(add) | reinterpret_cast<uintptr_t>(add2)) & 15u) == 0;
     if (al16 && (D == 1152 || D == 384 || D == 768 || D == 1024 || D == 128)) {
         switch (D / 128) {
-        case 1: launch_ln4_inst<1>(resid, add, shift, scale, mod_ld, rows_per_slot, M, out, out_f32, st); break;
-        case 3: launch_ln4_inst<3>(resid, add, shift, scale, mod_ld, rows_per_slot, M, out, out_f32, st); break;
-        case 6: launch_ln4_inst<6>(resid, add, shift, scale, mod_ld, rows_per_slot, M, out, out_f32, st); break;
-        case 8: launch_ln4_inst<8>(resid, add, shift, scale, mod_ld, rows_per_slot, M, out, out_f32, st); break;
-        default: launch_ln4_inst<9>(resid, add, shift, scale, mod_ld, rows_per_slot, M, out, out_f32, st); break;
+        case 1: launch_ln4_inst<1>(resid, add, add2, wb, shift, scale, mod_ld, rows_per_slot, M, out, out_f32, st); break;
+        case 3: launch_ln4_inst<3>(resid, add, add2, wb, shift, scale, mod_ld, rows_per_slot, M, out, out_f32, st); break;
+        case 6: launch_ln4_inst<6>(resid, add, add2, wb, shift, scale, mod_ld, rows_per_slot, M, out, out_f32, st); break;
+        case 8: launch_ln4_inst<8>(resid, add, add2, wb, shift, scale, mod_ld, rows_per_slot, M, out, out_f32, st); break;
+        default: launch_ln4_inst<9>(resid, add, add2, wb, shift, scale, mod_ld, rows_per_slot, M, out, out_f32, st); break;
         }
         DRF_HIP(hipGetLastError());
         return DRF_OK;
     }
     const int per = (D / 2 + kWave - 1) / kWave;      // column pairs per lane
-    if (per <= 1) launch_ln_inst<1>(resid, add, shift, scale, mod_ld, rows_per_slot, M, D, out, out_f32, st);
-    else if (per <= 3) launch_ln_inst<3>(resid, add, shift, scale, mod_ld, rows_per_slot, M, D, out, out_f32, st);
-    else if (per <= 5) launch_ln_inst<5>(resid, add, shift, scale, mod_ld, rows_per_slot, M, D, out, out_f32, st);
-    else if (per <= 9) launch_ln_inst<9>(resid, add, shift, scale, mod_ld, rows_per_slot, M, D, out, out_f32, st);
-    else launch_ln_inst<16>(resid, add, shift, scale, mod_ld, rows_per_slot, M, D, out, out_f32, st);
+    if (per <= 1) launch_ln_inst<1>(resid, add, add2, wb, shift, scale, mod_ld, rows_per_slot, M, D, out, out_f32, st);
+    else if (per <= 3) launch_ln_inst<3>(resid, add, add2, wb, shift, scale, mod_ld, rows_per_slot, M, D, out, out_f32, st);
+    else if (per <= 5) launch_ln_inst<5>(resid, add, add2, wb, shift, scale, mod_ld, rows_per_slot, M, D, out, out_f32, st);
+    else if (per <= 9) launch_ln_inst<9>(resid, add, add2, wb, shift, scale, mod_ld, rows_per_slot, M, D, out, out_f32, st);
+    else launch_ln_inst<16>(resid, add, add2, wb, shift, scale, mod_ld, rows_per_slot, M, D, out, out_f32, st);
     DRF_HIP(hipGetLastError());
     return DRF_OK;
 }
