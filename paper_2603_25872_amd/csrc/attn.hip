@@ -6,7 +6,6 @@
 #include <type_traits>
 
 #include "common.h"
-#include <cstdlib>
 
 namespace drf {
 
@@ -320,17 +319,12 @@ drf_status launch_bf16_cfg(const AttnArgs& a, float scale_log2, hipStream_t st)
 template <int KS, int DT>
 drf_status launch_bf16_inst(const AttnArgs& a, float scale_log2, hipStream_t st)
 {
-    // 8 waves (256 queries) share each staged chunk when there are that many queries; up to 256 kv
-    // rows go through one buffer of 128 rows refilled in place (measured slightly faster than staging
-    // all 256 at once: the first MFMAs start after half the loads), longer sequences through two
-    // buffers of 128 rows
-    if (const char* ev = getenv("DRF_ATTN")) {
-        const int c = atoi(ev);
-        if (c == 1) return launch_bf16_cfg<KS, DT, 8, 128, 2>(a, scale_log2, st);
-        if (c == 2) return launch_bf16_cfg<KS, DT, 8, 64, 2>(a, scale_log2, st);
-    }
+    // 8 waves (256 queries) share each staged chunk when there are that many queries.  Up to 256 kv rows
+    // go through two buffers of 64 rows (the first MFMAs start after a quarter of the loads and every
+    // later chunk is fetched during the steps of the one before; measured the fastest of the 64 / 128 /
+    // 256-row, one / two-buffer combinations), longer sequences through two buffers of 128 rows.
     if (a.Nq > 128) {
-        if (a.Nk <= 256) return launch_bf16_cfg<KS, DT, 8, 128, 1>(a, scale_log2, st);
+        if (a.Nk <= 256) return launch_bf16_cfg<KS, DT, 8, 64, 2>(a, scale_log2, st);
         return launch_bf16_cfg<KS, DT, 8, 128, 2>(a, scale_log2, st);
     }
     if (a.Nk <= 256) return launch_bf16_cfg<KS, DT, 4, 256, 1>(a, scale_log2, st);
