@@ -23,6 +23,7 @@ __device__ inline float max3(float a, float b, float c)
     asm("v_max3_f32 %0, %1, %2, %3" : "=v"(r) : "v"(a), "v"(b), "v"(c));
     return r;
 }
+constexpr int kPersistGroups = 256;  // workgroups of a persistent launch: one per CU of the MI355X
 constexpr float kTau = 8.f;         // lazy-rescale headroom of the online softmax, in log2 units
 
 // KS = ceil(d / 16) k-steps of the score MFMA; DT = ceil(d / 32) row tiles of O^T; NW waves of 32
@@ -38,9 +39,14 @@ constexpr float kTau = 8.f;         // lazy-rescale headroom of the online softm
 // V^T is stored with the 16 kv rows of each k-chunk permuted to [0-3, 8-11 | 4-7, 12-15]: that is
 // the order in which the score MFMA leaves a lane's P values, so the PV operand is one 16-byte read,
 // and the transposing store of four kv rows of one d is one 8-byte write.
-template <int KS, int DT, int NW, int KC, int NB>
-__global__ void __launch_bounds__(NW * 64) attn_bf16_kernel(const AttnArgs a, float scale_log2)
+// The grid is one-dimensional over work items (query block, head, slot), query block fastest.  With
+// PERSIST a workgroup takes items blockIdx.x, blockIdx.x + gridDim.x, ... and, while it runs the steps
+// of an item's last chunk, already has the next item's Q fragments and first K / V chunk in flight, so
+// only the first item of a workgroup waits for its first loads with nothing else to do.
+template <int KS, int DT, int NW, int KC, int NB, bool PERSIST>
+__global__ void __launch_bounds__(NW * 64) attn_bf16_kernel(const AttnArgs a, float scale_log2, int nqb, int n_items)
 {
+    static_assert(!PERSIST || NB == 2, "the cross-item prefetch needs two chunk buffers");
     constexpr int NT = NW * 64;
     constexpr int DK = KS * 16, LDKS = DK + 8, LDV = KC + 8;
     constexpr int KBUF = KC * LDKS, VBUF = DT * 32 * LDV;
@@ -50,12 +56,32 @@ __global__ void __launch_bounds__(NW * 64) attn_bf16_kernel(const AttnArgs a, fl
     bf16_t* sK = reinterpret_cast<bf16_t*>(attn_smem);                    // [buf][kv][d padded]
     bf16_t* sVt = sK + NB * KBUF;                                         // [buf][d padded][kv, permuted]
     const int tid = threadIdx.x, lane = tid & 63, wave = tid >> 6, l32 = lane & 31, half = lane >> 5;
-    const int slot = blockIdx.z, h = blockIdx.y, d = a.d;
-    const int kvb = a.kv_mod ? slot % a.kv_mod : slot;
-    const bf16_t* Q = (const bf16_t*)a.q + slot * a.q_slot_stride + h * a.q_head_stride;
-    const bf16_t* Kp = (const bf16_t*)a.k + kvb * a.kv_batch_stride + h * a.kv_head_stride;
-    const bf16_t* Vp = (const bf16_t*)a.v + kvb * a.kv_batch_stride + h * a.kv_head_stride;
+    const int d = a.d;
     const bf16x8 zero8 = { 0, 0, 0, 0, 0, 0, 0, 0 };
+    // where a work item's rows are, and this lane's query in it
+    struct Item { const bf16_t *Q, *Kp, *Vp; int slot, h, q; };
+    auto locate = [&](int item) {
+        Item it;
+        const int qb = item % nqb, hs = item / nqb;
+        it.h = hs % a.heads; it.slot = hs / a.heads;
+        const int kvb = a.kv_mod ? it.slot % a.kv_mod : it.slot;
+        it.Q = (const bf16_t*)a.q + it.slot * a.q_slot_stride + it.h * a.q_head_stride;
+        it.Kp = (const bf16_t*)a.k + kvb * a.kv_batch_stride + it.h * a.kv_head_stride;
+        it.Vp = (const bf16_t*)a.v + kvb * a.kv_batch_stride + it.h * a.kv_head_stride;
+        it.q = qb * (NW * 32) + wave * 32 + l32;
+        return it;
+    };
+    // this lane's Q fragments of an item (B operand: 8 consecutive d per k-step half)
+    auto load_q = [&](const Item& it, bf16x8 (&f)[KS]) {
+        const int qc = it.q < a.Nq ? it.q : a.Nq - 1;
+#pragma unroll
+        for (int ks = 0; ks < KS; ++ks) {
+            const int dd = ks * 16 + half * 8;
+            f[ks] = dd < d ? *reinterpret_cast<const bf16x8*>(it.Q + (size_t)qc * a.ldq + dd) : zero8;
+        }
+    };
+    int item = blockIdx.x;
+    Item cur = locate(item);
 
     // zero the padding that loads never touch: K columns [d, DK), V^T rows [d, DT*32)
     for (int i = tid; i < NB * (KBUF + VBUF) / 8; i += NT) reinterpret_cast<bf16x8*>(sK)[i] = zero8;
@@ -66,33 +92,22 @@ __global__ void __launch_bounds__(NW * 64) attn_bf16_kernel(const AttnArgs a, fl
     if (ones_row)
         for (int i = tid; i < NB * LDV; i += NT) sVt[(i / LDV) * VBUF + d * LDV + i % LDV] = (bf16_t)1.f;
 
-    // this lane's query column and its Q fragments (B operand: 8 consecutive d per k-step half)
-    const int q = blockIdx.x * (NW * 32) + wave * 32 + l32;
-    const int qc = q < a.Nq ? q : a.Nq - 1;
     bf16x8 qf[KS];
-#pragma unroll
-    for (int ks = 0; ks < KS; ++ks) {
-        const int dd = ks * 16 + half * 8;
-        qf[ks] = dd < d ? *reinterpret_cast<const bf16x8*>(Q + (size_t)qc * a.ldq + dd) : zero8;
-    }
+    load_q(cur, qf);
     f32x16 o[DT];
-#pragma unroll
-    for (int t = 0; t < DT; ++t)
-#pragma unroll
-        for (int r = 0; r < 16; ++r) o[t][r] = 0.f;
-    float m_run = -INFINITY, l_run = 0.f;      // running max of the raw scores, running sum
+    float m_run, l_run;                         // running max of the raw scores, running sum
     const int dch = d / 8, nch = KC * dch, nvb = (KC / 4) * dch;
 
     // K: consecutive threads take consecutive 16-byte pieces of a row (coalesced loads, 16-byte LDS
     // writes).  V: a thread takes 4 consecutive kv rows of one 8-wide d piece and writes, for each
     // of the 8 d, the 4 kv values as one 8-byte piece of the V^T row.
     bf16x8 rk[MAXK], rv[MAXV][4];
-    auto fetch = [&](int kv0) {
+    auto fetch = [&](const Item& it, int kv0) {
 #pragma unroll
         for (int c = 0; c < MAXK; ++c) {
             const int id = tid + c * NT, r = id / dch, cc = id % dch;
             rk[c] = zero8;
-            if (id < nch && kv0 + r < a.Nk) rk[c] = *reinterpret_cast<const bf16x8*>(Kp + (size_t)(kv0 + r) * a.ldk + cc * 8);
+            if (id < nch && kv0 + r < a.Nk) rk[c] = *reinterpret_cast<const bf16x8*>(it.Kp + (size_t)(kv0 + r) * a.ldk + cc * 8);
         }
 #pragma unroll
         for (int c = 0; c < MAXV; ++c) {
@@ -101,7 +116,7 @@ __global__ void __launch_bounds__(NW * 64) attn_bf16_kernel(const AttnArgs a, fl
             for (int j = 0; j < 4; ++j) {
                 rv[c][j] = zero8;
                 if (id < nvb && kv0 + 4 * g4 + j < a.Nk)
-                    rv[c][j] = *reinterpret_cast<const bf16x8*>(Vp + (size_t)(kv0 + 4 * g4 + j) * a.ldk + cc * 8);
+                    rv[c][j] = *reinterpret_cast<const bf16x8*>(it.Vp + (size_t)(kv0 + 4 * g4 + j) * a.ldk + cc * 8);
             }
         }
     };
@@ -213,59 +228,83 @@ __global__ void __launch_bounds__(NW * 64) attn_bf16_kernel(const AttnArgs a, fl
     // which would expose the loads of the chunk being prefetched.
 #pragma unroll
     for (int ks = 0; ks < KS; ++ks) asm volatile("" : "+v"(qf[ks]));
-    fetch(0);
+    fetch(cur, 0);
     __syncthreads();                            // zero fill and ones row done
     stage(0);
     __syncthreads();
     int buf = 0;
-    for (int c0 = 0; c0 < a.Nk; c0 += KC) {
-        // chunk c0 is visible in `buf`; with two buffers the next chunk is fetched now and staged
-        // after this chunk's steps (the other buffer was last read before the previous barrier)
-        const bool more = c0 + KC < a.Nk;
-        if (NB == 2 && more) fetch(c0 + KC);
-        const bf16_t* bk = sK + buf * KBUF;
-        const bf16_t* bv = sVt + buf * VBUF;
-        for (int r0 = 0; r0 < KC && c0 + r0 < a.Nk; r0 += kKvb) step(bk, bv, r0, c0 + r0);
-        if (more) {
-            if (NB == 2) {
-                stage(buf ^ 1);
-                buf ^= 1;
-            } else {                            // single buffer: refill in place
+    for (;;) {
+        const int nxt = item + (int)gridDim.x;
+        const bool has_next = PERSIST && nxt < n_items;
+        Item np = cur;
+#pragma unroll
+        for (int t = 0; t < DT; ++t)
+#pragma unroll
+            for (int r = 0; r < 16; ++r) o[t][r] = 0.f;
+        m_run = -INFINITY; l_run = 0.f;
+        for (int c0 = 0; c0 < a.Nk; c0 += KC) {
+            // chunk c0 is visible in `buf`; with two buffers the next chunk (of this item, or the first
+            // one of the workgroup's next item together with that item's Q fragments) is fetched now and
+            // staged after this chunk's steps (the other buffer was last read before the previous barrier)
+            const bool more = c0 + KC < a.Nk;
+            if (NB == 2 && more) fetch(cur, c0 + KC);
+            if (PERSIST && !more && has_next) {
+                np = locate(nxt);
+                fetch(np, 0);
+            }
+            const bf16_t* bk = sK + buf * KBUF;
+            const bf16_t* bv = sVt + buf * VBUF;
+            for (int r0 = 0; r0 < KC && c0 + r0 < a.Nk; r0 += kKvb) step(bk, bv, r0, c0 + r0);
+            if (PERSIST && !more && has_next) {     // the old fragments are dead: the next item's take their place
+                load_q(np, qf);
+#pragma unroll
+                for (int ks = 0; ks < KS; ++ks) asm volatile("" : "+v"(qf[ks]));
+            }
+            if (more || has_next) {
+                if (NB == 2) {
+                    stage(buf ^ 1);
+                    buf ^= 1;
+                } else {                        // single buffer: refill in place
+                    __syncthreads();
+                    fetch(cur, c0 + KC);
+                    stage(0);
+                }
                 __syncthreads();
-                fetch(c0 + KC);
-                stage(0);
-            }
-            __syncthreads();
-        }
-    }
-    // denominator: from the ones row (kept by the lanes of one half) or the two halves' partial sums
-    float l_tot;
-    if (ones_row) {
-        const int tt = d >> 5, lr = d & 31, r = 4 * (lr >> 3) + (lr & 3), owner = (lr >> 2) & 1;
-        float mine = 0.f;
-#pragma unroll
-        for (int t2 = 0; t2 < DT; ++t2)
-#pragma unroll
-            for (int r2 = 0; r2 < 16; ++r2) mine = (t2 == tt && r2 == r) ? o[t2][r2] : mine;
-        const float other = __shfl_xor(mine, 32, 64);
-        l_tot = half == owner ? mine : other;
-    } else {
-        l_tot = l_run + __shfl_xor(l_run, 32, 64);
-    }
-    if (q >= a.Nq) return;
-    const float inv = 1.f / l_tot;
-    bf16_t* op = (bf16_t*)a.out + ((size_t)slot * a.Nq + q) * a.ldo + h * d;
-#pragma unroll
-    for (int tt = 0; tt < DT; ++tt)
-#pragma unroll
-        for (int g4 = 0; g4 < 4; ++g4) {
-            const int dd = tt * 32 + 8 * g4 + 4 * half;
-            if (dd < d) {
-                bf16x4 w = { (bf16_t)(o[tt][4 * g4] * inv), (bf16_t)(o[tt][4 * g4 + 1] * inv),
-                             (bf16_t)(o[tt][4 * g4 + 2] * inv), (bf16_t)(o[tt][4 * g4 + 3] * inv) };
-                *reinterpret_cast<bf16x4*>(op + dd) = w;
             }
         }
+        // denominator: from the ones row (kept by the lanes of one half) or the two halves' partial sums
+        float l_tot;
+        if (ones_row) {
+            const int tt = d >> 5, lr = d & 31, r = 4 * (lr >> 3) + (lr & 3), owner = (lr >> 2) & 1;
+            float mine = 0.f;
+#pragma unroll
+            for (int t2 = 0; t2 < DT; ++t2)
+#pragma unroll
+                for (int r2 = 0; r2 < 16; ++r2) mine = (t2 == tt && r2 == r) ? o[t2][r2] : mine;
+            const float other = __shfl_xor(mine, 32, 64);
+            l_tot = half == owner ? mine : other;
+        } else {
+            l_tot = l_run + __shfl_xor(l_run, 32, 64);
+        }
+        if (cur.q < a.Nq) {
+            const float inv = 1.f / l_tot;
+            bf16_t* op = (bf16_t*)a.out + ((size_t)cur.slot * a.Nq + cur.q) * a.ldo + cur.h * d;
+#pragma unroll
+            for (int tt = 0; tt < DT; ++tt)
+#pragma unroll
+                for (int g4 = 0; g4 < 4; ++g4) {
+                    const int dd = tt * 32 + 8 * g4 + 4 * half;
+                    if (dd < d) {
+                        bf16x4 w = { (bf16_t)(o[tt][4 * g4] * inv), (bf16_t)(o[tt][4 * g4 + 1] * inv),
+                                     (bf16_t)(o[tt][4 * g4 + 2] * inv), (bf16_t)(o[tt][4 * g4 + 3] * inv) };
+                        *reinterpret_cast<bf16x4*>(op + dd) = w;
+                    }
+                }
+        }
+        if (!has_next) break;
+        item = nxt;
+        cur = np;
+    }
 }
 
 // fp32: one thread per query, online softmax over kv rows read through the cache.
@@ -298,20 +337,24 @@ __global__ void __launch_bounds__(128) attn_f32_kernel(const AttnArgs a, float s
     for (int e = 0; e < d; ++e) op[e] = o[e] * inv;
 }
 
-template <int KS, int DT, int NW, int KC, int NB>
+template <int KS, int DT, int NW, int KC, int NB, bool PERSIST = false>
 drf_status launch_bf16_cfg(const AttnArgs& a, float scale_log2, hipStream_t st)
 {
     constexpr int LDKS = KS * 16 + 8, LDV = KC + 8;
     constexpr size_t smem = (size_t)NB * (KC * LDKS + DT * 32 * LDV) * sizeof(bf16_t);
     static_assert(smem <= 160 * 1024 && smem % 16 == 0, "LDS budget");
-    auto kern = attn_bf16_kernel<KS, DT, NW, KC, NB>;
+    auto kern = attn_bf16_kernel<KS, DT, NW, KC, NB, PERSIST>;
     static bool attr_set = false;
     if (!attr_set) {
         DRF_HIP(hipFuncSetAttribute(reinterpret_cast<const void*>(kern), hipFuncAttributeMaxDynamicSharedMemorySize, (int)smem));
         attr_set = true;
     }
-    const dim3 grid((a.Nq + NW * 32 - 1) / (NW * 32), a.heads, a.slots);
-    hipLaunchKernelGGL(kern, grid, dim3(NW * 64), smem, st, a, scale_log2);
+    const int nqb = (a.Nq + NW * 32 - 1) / (NW * 32);
+    const long long n_items = (long long)nqb * a.heads * a.slots;
+    if (n_items > 0x7fffffffLL) DRF_FAIL(DRF_ESHAPE, "attention: too many (query block, head, slot) items");
+    // persistent: one workgroup per CU-sized share (a workgroup of 8 waves fills a CU)
+    const int grid = PERSIST && n_items > kPersistGroups ? kPersistGroups : (int)n_items;
+    hipLaunchKernelGGL(kern, dim3(grid), dim3(NW * 64), smem, st, a, scale_log2, nqb, (int)n_items);
     DRF_HIP(hipGetLastError());
     return DRF_OK;
 }
@@ -324,7 +367,13 @@ drf_status launch_bf16_inst(const AttnArgs& a, float scale_log2, hipStream_t st)
     // later chunk is fetched during the steps of the one before; measured the fastest of the 64 / 128 /
     // 256-row, one / two-buffer combinations), longer sequences through two buffers of 128 rows.
     if (a.Nq > 128) {
-        if (a.Nk <= 256) return launch_bf16_cfg<KS, DT, 8, 64, 2>(a, scale_log2, st);
+        if (a.Nk <= 256) {
+            // more items than workgroups that fit the chip at once: persistent workgroups hide each next
+            // item's first loads; otherwise the plain kernel (fewer registers) is the faster one
+            const long long n_items = (long long)((a.Nq + 255) / 256) * a.heads * a.slots;
+            if (n_items > kPersistGroups) return launch_bf16_cfg<KS, DT, 8, 64, 2, true>(a, scale_log2, st);
+            return launch_bf16_cfg<KS, DT, 8, 64, 2>(a, scale_log2, st);
+        }
         return launch_bf16_cfg<KS, DT, 8, 128, 2>(a, scale_log2, st);
     }
     if (a.Nk <= 256) return launch_bf16_cfg<KS, DT, 4, 256, 1>(a, scale_log2, st);

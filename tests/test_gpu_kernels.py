@@ -53,7 +53,8 @@ def test_gemm_bf16_rejects_bad_k(torch, drf):
 
 
 @pytest.mark.parametrize("slots,T,H,d", [(3, 256, 2, 72), (2, 77, 3, 64), (5, 15, 4, 32), (1, 300, 1, 96), (2, 130, 2, 48),
-                                          (1, 1, 2, 16), (2, 192, 1, 80), (1, 129, 1, 80), (2, 640, 2, 72), (1, 255, 2, 24)])
+                                          (1, 1, 2, 16), (2, 192, 1, 80), (1, 129, 1, 80), (2, 640, 2, 72), (1, 255, 2, 24),
+                                          (40, 200, 8, 72), (65, 136, 4, 40)])     # more work items than CUs
 def test_attention_bf16_shapes(torch, drf, orc, slots, T, H, d):
     rng = np.random.default_rng(T + d)
     qkv = bf16_round(torch, rng.standard_normal((slots * T, 3 * H * d)) * 1.5)
