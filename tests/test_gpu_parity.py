@@ -163,6 +163,16 @@ def test_bf16_text_cross_attention_77(torch, drf, orc):
     check_forward(torch, drf, orc, dit, "loud", slots=2, tol=TOL_BF16, seed=31)
 
 
+def test_bf16_attention_with_more_work_items_than_cus(torch, drf, orc):
+    # launches whose (query block, head, slot) items outnumber the CUs run persistent workgroups:
+    # self-attention over a ragged 200-token sequence, and cross-attention of 1024 queries (four
+    # query blocks per head) against a 77-row context
+    dit = small_dit(I.COND_CLASS, I.BF16, depth=1, lat_h=20, lat_w=40)
+    check_forward(torch, drf, orc, dit, "loud", slots=70, tol=TOL_BF16, seed=41, trace=False)
+    dit = small_dit(I.COND_TEXT, I.BF16, depth=1, lat_h=64, lat_w=64, ctx_len=77)
+    check_forward(torch, drf, orc, dit, "loud", slots=17, tol=TOL_BF16, seed=42, trace=False)
+
+
 def test_eps_batched_edge_cases(torch, drf):
     dit = small_dit(I.COND_CLASS, I.F32, depth=1)
     den = drf.Denoiser(dit, I.weights(dit, 2))
