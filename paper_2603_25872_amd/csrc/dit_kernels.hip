@@ -358,6 +358,84 @@ __global__ void __launch_bounds__(256) final_kernel(const float* __restrict__ re
     }
 }
 
+// Final layer for hidden sizes that are multiples of 128 and weights [P][D] that fit LDS: the weights are
+// staged once per block, half a wave takes a row (16-byte loads, the row stays in registers through the
+// statistics, the modulation and the P dot products), and 16 partial sums per lane are reduced across
+// the half wave by a transposing butterfly (8 + 4 + 2 + 1 + 1 exchanges) that leaves output k on the lane
+// whose bits 4..1 spell k.
+template <int PER4>
+__global__ void __launch_bounds__(256) final4_kernel(const float* __restrict__ resid, const float* __restrict__ shift,
+                                                     const float* __restrict__ scale, int mod_ld,
+                                                     const float* __restrict__ w, const float* __restrict__ b,
+                                                     const DitDims dm, int M, int rows_per_block, float* __restrict__ eps_out)
+{
+    constexpr int D = PER4 * 128;
+    extern __shared__ __attribute__((aligned(16))) float fin_w[];            // [P][D]
+    const int P = dm.P, tid = threadIdx.x, l32 = tid & 31, hw = tid >> 5;
+    for (int i = tid; i < P * (D / 4); i += 256) reinterpret_cast<float4*>(fin_w)[i] = reinterpret_cast<const float4*>(w)[i];
+    __syncthreads();
+    const size_t E = (size_t)dm.C * dm.H * dm.W;
+    const int pp = dm.patch * dm.patch;
+    const int row0 = blockIdx.x * rows_per_block, row_end = min(M, row0 + rows_per_block);
+    for (int row = row0 + hw; row < row_end; row += 8) {
+        const float4* xr = reinterpret_cast<const float4*>(resid + (size_t)row * D);
+        float4 v[PER4];
+        float sum = 0.f;
+#pragma unroll
+        for (int i = 0; i < PER4; ++i) {
+            v[i] = xr[i * 32 + l32];
+            sum += (v[i].x + v[i].y) + (v[i].z + v[i].w);
+        }
+        const float mean = half_wave_sum(sum) * (1.f / (float)D);
+        float sq = 0.f;
+#pragma unroll
+        for (int i = 0; i < PER4; ++i) {
+            const float dx = v[i].x - mean, dy = v[i].y - mean, dz = v[i].z - mean, dw = v[i].w - mean;
+            sq = fmaf(dx, dx, fmaf(dy, dy, fmaf(dz, dz, fmaf(dw, dw, sq))));
+        }
+        const float rstd = rsqrtf(half_wave_sum(sq) * (1.f / (float)D) + 1e-6f);
+        const int slot = row / dm.T, t = row % dm.T, py = t / dm.gw, px = t % dm.gw;
+        const float4* sh = reinterpret_cast<const float4*>(shift + (size_t)slot * mod_ld);
+        const float4* sc = reinterpret_cast<const float4*>(scale + (size_t)slot * mod_ld);
+#pragma unroll
+        for (int i = 0; i < PER4; ++i) {
+            const float4 s4 = sc[i * 32 + l32], h4 = sh[i * 32 + l32];
+            v[i].x = fmaf((v[i].x - mean) * rstd, 1.f + s4.x, h4.x); v[i].y = fmaf((v[i].y - mean) * rstd, 1.f + s4.y, h4.y);
+            v[i].z = fmaf((v[i].z - mean) * rstd, 1.f + s4.z, h4.z); v[i].w = fmaf((v[i].w - mean) * rstd, 1.f + s4.w, h4.w);
+        }
+        for (int kbase = 0; kbase < P; kbase += 16) {
+            float acc[16];
+#pragma unroll
+            for (int q = 0; q < 16; ++q) {
+                acc[q] = 0.f;
+                if (kbase + q < P) {                        // uniform over the block
+                    const float4* wk = reinterpret_cast<const float4*>(fin_w + (size_t)(kbase + q) * D);
+#pragma unroll
+                    for (int i = 0; i < PER4; ++i) {
+                        const float4 w4 = wk[i * 32 + l32];
+                        acc[q] = fmaf(v[i].x, w4.x, fmaf(v[i].y, w4.y, fmaf(v[i].z, w4.z, fmaf(v[i].w, w4.w, acc[q]))));
+                    }
+                }
+            }
+            float a8[8], a4[4], a2[2];
+            const bool b16 = l32 & 16, b8 = l32 & 8, b4 = l32 & 4, b2 = l32 & 2;
+#pragma unroll
+            for (int q = 0; q < 8; ++q) a8[q] = (b16 ? acc[q + 8] : acc[q]) + __shfl_xor(b16 ? acc[q] : acc[q + 8], 16, 64);
+#pragma unroll
+            for (int q = 0; q < 4; ++q) a4[q] = (b8 ? a8[q + 4] : a8[q]) + __shfl_xor(b8 ? a8[q] : a8[q + 4], 8, 64);
+#pragma unroll
+            for (int q = 0; q < 2; ++q) a2[q] = (b4 ? a4[q + 2] : a4[q]) + __shfl_xor(b4 ? a4[q] : a4[q + 2], 4, 64);
+            const float a1 = (b2 ? a2[1] : a2[0]) + __shfl_xor(b2 ? a2[0] : a2[1], 2, 64);
+            const float tot = a1 + __shfl_xor(a1, 1, 64);
+            const int k = kbase + (b16 ? 8 : 0) + (b8 ? 4 : 0) + (b4 ? 2 : 0) + (b2 ? 1 : 0);
+            if (!(l32 & 1) && k < P) {
+                const int ch = k / pp, dy = (k % pp) / dm.patch, dx = k % dm.patch;
+                eps_out[(size_t)slot * E + ((size_t)ch * dm.H + py * dm.patch + dy) * dm.W + px * dm.patch + dx] = tot + b[k];
+            }
+        }
+    }
+}
+
 __global__ void f32_to_bf16_kernel(const float* __restrict__ in, bf16_t* __restrict__ out, size_t n)
 {
     const size_t stride = (size_t)gridDim.x * blockDim.x;
@@ -471,6 +549,30 @@ drf_status launch_final(const float* resid, const float* shift, const float* sca
     const int M = slots * dm.T;
     if (M == 0) return DRF_OK;
     if (dm.D > 2048) DRF_FAIL(DRF_ESHAPE, "final layer needs hidden <= 2048");
+    const size_t wbytes = (size_t)dm.P * dm.D * sizeof(float);
+    const bool al16 = mod_ld % 4 == 0 && ((reinterpret_cast<uintptr_t>(resid) | reinterpret_cast<uintptr_t>(shift) |
+                                           reinterpret_cast<uintptr_t>(scale) | reinterpret_cast<uintptr_t>(w)) & 15u) == 0;
+    if (al16 && wbytes <= 96 * 1024 && (dm.D == 1152 || dm.D == 384 || dm.D == 768 || dm.D == 1024 || dm.D == 128)) {
+        const int rpb = M >= 8192 ? 32 : 16;
+        const dim3 grid4((M + rpb - 1) / rpb), block4(256);
+        auto go = [&](auto kern) -> drf_status {
+            static bool attr_set = false;                   // one flag per kernel instantiation
+            if (!attr_set) {
+                DRF_HIP(hipFuncSetAttribute(reinterpret_cast<const void*>(kern), hipFuncAttributeMaxDynamicSharedMemorySize, 96 * 1024));
+                attr_set = true;
+            }
+            hipLaunchKernelGGL(kern, grid4, block4, wbytes, st, resid, shift, scale, mod_ld, w, b, dm, M, rpb, eps_out);
+            DRF_HIP(hipGetLastError());
+            return DRF_OK;
+        };
+        switch (dm.D / 128) {
+        case 1: return go(final4_kernel<1>);
+        case 3: return go(final4_kernel<3>);
+        case 6: return go(final4_kernel<6>);
+        case 8: return go(final4_kernel<8>);
+        default: return go(final4_kernel<9>);
+        }
+    }
     const dim3 grid((M + kFinalRowsPerBlock - 1) / kFinalRowsPerBlock), block(256);
     const int per = (dm.D + kWave - 1) / kWave;
     if (per <= 6) hipLaunchKernelGGL(final_kernel<6>, grid, block, 0, st, resid, shift, scale, mod_ld, w, b, dm, M, eps_out);
