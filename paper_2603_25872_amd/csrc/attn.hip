@@ -55,6 +55,8 @@ __global__ void __launch_bounds__(NW * 64) attn_bf16_kernel(const AttnArgs a, fl
     extern __shared__ __attribute__((aligned(16))) unsigned char attn_smem[];
     bf16_t* sK = reinterpret_cast<bf16_t*>(attn_smem);                    // [buf][kv][d padded]
     bf16_t* sVt = sK + NB * KBUF;                                         // [buf][d padded][kv, permuted]
+    constexpr int LDO = DT * 32 + 8;                                      // row stride of a wave's output tile
+    bf16_t* sOut = sVt + NB * VBUF + (threadIdx.x >> 6) * (32 * LDO);     // [wave][32 queries][d padded]
     const int tid = threadIdx.x, lane = tid & 63, wave = tid >> 6, l32 = lane & 31, half = lane >> 5;
     const int d = a.d;
     const bf16x8 zero8 = { 0, 0, 0, 0, 0, 0, 0, 0 };
@@ -286,20 +288,28 @@ __global__ void __launch_bounds__(NW * 64) attn_bf16_kernel(const AttnArgs a, fl
         } else {
             l_tot = l_run + __shfl_xor(l_run, 32, 64);
         }
-        if (cur.q < a.Nq) {
+        // The wave's 32 x d output tile goes through its own LDS slice so that global memory is written
+        // in 16-byte pieces of whole rows (a lane holds 4 consecutive d of one query: stored directly,
+        // every instruction would touch 32 different rows).  LDS operations of a wave complete in order,
+        // so the reads below see the writes without a barrier.
+        {
             const float inv = 1.f / l_tot;
-            bf16_t* op = (bf16_t*)a.out + ((size_t)cur.slot * a.Nq + cur.q) * a.ldo + cur.h * d;
 #pragma unroll
             for (int tt = 0; tt < DT; ++tt)
 #pragma unroll
                 for (int g4 = 0; g4 < 4; ++g4) {
                     const int dd = tt * 32 + 8 * g4 + 4 * half;
-                    if (dd < d) {
-                        bf16x4 w = { (bf16_t)(o[tt][4 * g4] * inv), (bf16_t)(o[tt][4 * g4 + 1] * inv),
-                                     (bf16_t)(o[tt][4 * g4 + 2] * inv), (bf16_t)(o[tt][4 * g4 + 3] * inv) };
-                        *reinterpret_cast<bf16x4*>(op + dd) = w;
-                    }
+                    const bf16x4 w = { (bf16_t)(o[tt][4 * g4] * inv), (bf16_t)(o[tt][4 * g4 + 1] * inv),
+                                       (bf16_t)(o[tt][4 * g4 + 2] * inv), (bf16_t)(o[tt][4 * g4 + 3] * inv) };
+                    *reinterpret_cast<bf16x4*>(sOut + l32 * LDO + dd) = w;
                 }
+            const int q0 = cur.q - l32;                                   // first query of the wave's tile
+            bf16_t* op = (bf16_t*)a.out + ((size_t)cur.slot * a.Nq + q0) * a.ldo + cur.h * d;
+            for (int id = lane; id < 32 * dch; id += 64) {
+                const int r = id / dch, c = id % dch;
+                if (q0 + r < a.Nq)
+                    *reinterpret_cast<bf16x8*>(op + (size_t)r * a.ldo + c * 8) = *reinterpret_cast<const bf16x8*>(sOut + r * LDO + c * 8);
+            }
         }
         if (!has_next) break;
         item = nxt;
@@ -341,7 +351,7 @@ template <int KS, int DT, int NW, int KC, int NB, bool PERSIST = false>
 drf_status launch_bf16_cfg(const AttnArgs& a, float scale_log2, hipStream_t st)
 {
     constexpr int LDKS = KS * 16 + 8, LDV = KC + 8;
-    constexpr size_t smem = (size_t)NB * (KC * LDKS + DT * 32 * LDV) * sizeof(bf16_t);
+    constexpr size_t smem = ((size_t)NB * (KC * LDKS + DT * 32 * LDV) + (size_t)NW * 32 * (DT * 32 + 8)) * sizeof(bf16_t);
     static_assert(smem <= 160 * 1024 && smem % 16 == 0, "LDS budget");
     auto kern = attn_bf16_kernel<KS, DT, NW, KC, NB, PERSIST>;
     static bool attr_set = false;
@@ -385,7 +395,8 @@ drf_status launch_bf16_inst(const AttnArgs& a, float scale_log2, hipStream_t st)
 drf_status launch_attn_bf16(const AttnArgs& a, hipStream_t st)
 {
     if (a.slots == 0 || a.Nq == 0) return DRF_OK;
-    if (a.Nk < 1 || a.d % 8 != 0 || a.d > 96 || a.ldq % 8 != 0 || a.ldk % 8 != 0 || a.ldo % 4 != 0)
+    if (a.Nk < 1 || a.d % 8 != 0 || a.d > 96 || a.ldq % 8 != 0 || a.ldk % 8 != 0 || a.ldo % 8 != 0 ||
+        (reinterpret_cast<uintptr_t>(a.out) & 15u) != 0)
         DRF_FAIL(DRF_ESHAPE, "bf16 attention needs head dim %% 8 == 0 and <= 96 (got %d)", a.d);
     const float sl2 = 1.4426950408889634f / sqrtf((float)a.d);
     switch ((a.d + 15) / 16) {
