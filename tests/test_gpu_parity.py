@@ -2,6 +2,8 @@
 inputs.  Tolerances are the workload's: plan/timestep bookkeeping bit-exact (checked
 on the host in test_host_abi.py), fp32 path max-norm relative error <= 1e-4, bf16
 path <= 2e-2, where error = max|gpu - oracle| / max|oracle| per sample."""
+import os
+
 import numpy as np
 import pytest
 
@@ -241,6 +243,24 @@ def test_sample_bf16_guidance_head72(torch, drf, orc):
     cfg["sched"]["steps"] = 9
     run_sample(torch, drf, orc, cfg, TOL_BF16, n=4, batch=2)
     run_sample(torch, drf, orc, cfg, TOL_BF16, mode=I.AGGRESSIVE, n=4, batch=2, init="loud", seed=3)
+
+
+def test_sample_config3_full_depth_against_the_stored_oracle_sample(torch, drf):
+    """Configuration 3 exactly as benchmarked except for the batch (1 instead of 8: samples are
+    independent): 28 blocks, 50-step DDIM, conservative n = 4, guidance 4.  The expected x_0 was written by
+    tests/golden/make_cfg3_sample.py, which calls the CPU oracle only (about half an hour on 8 cores, so
+    it is stored instead of recomputed)."""
+    path = os.path.join(os.path.dirname(os.path.abspath(__file__)), "golden", "cfg3_batch1_x0.txt")
+    cfg = I.config(3)
+    dit, sd = cfg["dit"], cfg["sched"]
+    want = np.loadtxt(path).reshape(1, dit["in_ch"], dit["lat_h"], dit["lat_w"])
+    w = I.weights(dit, 3)
+    xT, cond, null = I.latent_noise(dit, 1, 3), I.conditioning(dit, 1, 3), I.conditioning(dit, 1, 3, null=True)
+    den = drf.Denoiser(dit, w)
+    got = den.sample(sd, cfg["mode"], cfg["n"], dev(torch, xT), dev(torch, cond), dev(torch, null), cfg["guidance"]).cpu().numpy()
+    den.close()
+    err = relerr(got, want)
+    assert np.isfinite(err) and err < TOL_BF16, err
 
 
 def test_sample_bf16_text_guidance(torch, drf, orc):
