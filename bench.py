@@ -71,7 +71,8 @@ def main():
         torch.cuda.synchronize()
         print(json.dumps({"copy_calibration": {"bytes_read_per_copy": 1 << 30, "bytes_written_per_copy": 1 << 30, "copies": 3}}))
         return
-    from paper_2603_25872_amd import drf, inputs as I
+    from paper_2603_25872_amd import build as lib_build, drf, inputs as I
+    lib_build.ensure_built()                       # loads what is built; compiles only if nothing is
 
     cfg = I.config(args.config)
     dit, sd = cfg["dit"], dict(cfg["sched"], sampler=args.sampler, eta=args.eta, shift=args.shift)

@@ -34,5 +34,13 @@ def build(verbose=False):
     return LIB
 
 
+def ensure_built():
+    """For the test harness, the smoke entry and the benchmark: compile only when no library has been
+    built yet.  The binding itself never builds: it raises when the library is missing."""
+    if not os.path.exists(LIB):
+        build(verbose=True)
+    return LIB
+
+
 if __name__ == "__main__":
     build(verbose=True)

@@ -12,6 +12,13 @@ def pytest_configure(config):
     config.addinivalue_line("markers", "gpu: needs a real MI355X (run with -m gpu)")
 
 
+@pytest.fixture(scope="session", autouse=True)
+def built_library():
+    # load what is built; compile only when nothing is (after a source change, build before running tests)
+    from paper_2603_25872_amd import build
+    return build.ensure_built()
+
+
 @pytest.fixture(scope="session")
 def orc():
     from oracle.ref import Oracle
