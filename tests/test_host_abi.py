@@ -143,3 +143,13 @@ def test_null_handles_are_rejected_without_touching_the_gpu():
     assert L.drf_skip_transition(C.byref(sc), None, None, 5, to, 1, 0, 16, None, None) == 0
     assert L.drf_skip_transition(C.byref(sc), None, None, 5, to, 1, 2, 16, None, None) == -1
     assert L.drf_refine_step(C.byref(sc), None, None, 0, 1, 16, None, None) == -1
+
+
+def test_bench_refuses_more_than_one_gpu():
+    # the contract: bench.py --gpus N with N > 1 exits with a message that says so (no GPU is touched)
+    import subprocess
+    import sys
+    root = os.path.dirname(os.path.dirname(os.path.abspath(__file__)))
+    r = subprocess.run([sys.executable, os.path.join(root, "bench.py"), "--gpus", "2"], capture_output=True, text=True)
+    assert r.returncode != 0
+    assert "one GPU" in (r.stderr + r.stdout)
