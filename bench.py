@@ -5,10 +5,13 @@ steps: batched DiT passes + fused guidance/refine/draft updates) over one batch 
 synthetic latents, inputs resident in HBM.  Default workload: configuration 3
 (DiT-XL/2-shaped, bf16, guidance 4, 50-step DDIM, conservative n=4, batch 8).
 
-Prints ONE JSON line: eps-evals/s over the whole call, ms per step, the roofline of the
-dominant kernel family (bf16 MFMA GEMM) measured with HIP events on the library's
-stream during one extra instrumented call, and the CPU oracle timed on a bounded
-sample of the same workload (one slot evaluation of the same DiT)."""
+Prints ONE JSON line: eps-evals/s over the whole call, ms per step; `roofline`: the full draft pass
+(all kernels of one batched predictor pass over the n draft groups: its algorithmic flops over its
+duration, measured with HIP events on the library's stream inside drf_sample during an extra
+instrumented call), with the bf16 GEMM launches alone as the sub-key `gemm`, the spec peak as `peak`
+and what this GPU delivers for an MFMA-only loop and a plain copy as `peak_measured`; and
+`cpu_baseline`: the CPU oracle timed on a bounded sample of the same workload (slot evaluations of
+the same DiT).  `--calibrate` prints only the measured ceilings."""
 import argparse
 import json
 import os
@@ -21,10 +24,23 @@ if ROOT not in sys.path:
 
 PEAK_BF16_TFLOPS = 2500.0     # MI355X dense bf16 MFMA
 PEAK_HBM_GBS = 8000.0
-# Bytes the bf16 GEMM launches of one configuration-3 call move past the L2, per launch on average: rocprofv3 FETCH_SIZE
-# and WRITE_SIZE, each scaled by what the same counter reads for a plain 1 GiB copy
-# (profiles/drf_sample_cfg3_pmc_traffic_mfma.txt).  Only valid for the default workload.
+# HBM-side bytes of the default workload from rocprofv3 --pmc runs (FETCH_SIZE and WRITE_SIZE, each scaled by what
+# the same counter reads for a plain 1 GiB copy; profiles/drf_sample_cfg3_pmc_traffic_mfma.txt): per full draft pass
+# (all kernels of one 64-slot pass) and per bf16 GEMM launch on average.  Counters cannot be read inside this
+# process, so these are the committed profile's figures and only reported for the workload they were measured on.
+PASS_TRAFFIC_BYTES = {3: None}
 GEMM_TRAFFIC_BYTES_PER_LAUNCH = {3: 1.873e8}
+
+
+def calibrate(torch, drf):
+    """What this GPU delivers for a loop of nothing but the GEMM kernel's MFMA instruction (random and constant
+    operands: the clock depends on operand toggling) and for a plain 1 GiB copy kernel."""
+    out = {"mfma_bf16_random_operands_TFLOPs": max(drf.calibrate_mfma_bf16(True, 5) for _ in range(2)),
+           "mfma_bf16_constant_operands_TFLOPs": max(drf.calibrate_mfma_bf16(False, 5) for _ in range(2))}
+    a = torch.empty(1 << 28, dtype=torch.float32, device="cuda").normal_()
+    b = torch.empty_like(a)
+    out["copy_1GiB_GBps"] = max(drf.calibrate_copy(a, b, 5) for _ in range(2))
+    return out
 
 
 def slot_eval_flops(dit):
@@ -53,6 +69,10 @@ def main():
     ap.add_argument("--seed", type=int, default=1, help="seed of the library's noise stream (stochastic samplers)")
     ap.add_argument("--no-cpu-baseline", action="store_true")
     ap.add_argument("--no-roofline", action="store_true")
+    ap.add_argument("--calibrate", action="store_true", help="only measure the MFMA-loop and copy-kernel ceilings of this GPU")
+    ap.add_argument("--update-probe", action="store_true",
+                    help="only run the fused update kernel (guidance, chain of n, n next drafts) at batch 4096: the launch a "
+                         "profiler run reads FETCH_SIZE / WRITE_SIZE for")
     ap.add_argument("--copy-calibration", action="store_true",
                     help="only run three plain 1 GiB device-to-device copies: the kernel of known size against "
                          "which the FETCH_SIZE / WRITE_SIZE counters of a profiler run are scaled")
@@ -73,6 +93,9 @@ def main():
         return
     from paper_2603_25872_amd import build as lib_build, drf, inputs as I
     lib_build.ensure_built()                       # loads what is built; compiles only if nothing is
+    if args.calibrate:
+        print(json.dumps({"peak_measured": calibrate(torch, drf)}))
+        return
 
     cfg = I.config(args.config)
     dit, sd = cfg["dit"], dict(cfg["sched"], sampler=args.sampler, eta=args.eta, shift=args.shift)
@@ -84,6 +107,32 @@ def main():
                         and args.eta == 0.0)
     g = 2 if cfg["guidance"] else 1
     assert torch.cuda.is_available(), "bench.py needs a GPU"
+
+    def update_probe(iters):
+        """The fused update kernel as drf_sample launches it after a full draft pass of the aggressive mode (guidance
+        combine of n (cond, null) field pairs, chain of n updates, n next drafts) on 4096 samples of this latent."""
+        E = dit["in_ch"] * dit["lat_h"] * dit["lat_w"]
+        big, nn = max(1, min(4096, (1 << 24) // E)), min(n, 4)
+        xb = torch.randn((big, E), device="cuda")
+        eb = torch.randn((nn, g, big, E), device="cuda")
+        xo = torch.empty_like(xb)
+        do = torch.empty((nn, big, E), device="cuda")
+        s_from = min(S, 2 * nn + 1)
+        nbytes = 4 * big * E * (1 + g * nn + 1 + nn)
+        drf.probe_update_fused(cfg["sched"], s_from, nn, nn, g, cfg["guidance"] or 0.0, xb, eb, xo, do)
+        e0, e1 = torch.cuda.Event(enable_timing=True), torch.cuda.Event(enable_timing=True)
+        e0.record()                                  # torch's current stream is the stream the library is given
+        for _ in range(iters):
+            drf.probe_update_fused(cfg["sched"], s_from, nn, nn, g, cfg["guidance"] or 0.0, xb, eb, xo, do)
+        e1.record()
+        torch.cuda.synchronize()
+        us = e0.elapsed_time(e1) * 1e3 / iters
+        return {"form": "guidance g=%d, chain of %d, %d next drafts" % (g, nn, nn), "batch": big, "bytes_per_launch": nbytes,
+                "us_per_launch": us, "achieved_GBps": nbytes / (us * 1e-6) / 1e9, "peak_GBps": PEAK_HBM_GBS}
+
+    if args.update_probe:
+        print(json.dumps({"update_kernel_fused_scaled": update_probe(3)}))
+        return
 
     w = I.weights(dit, args.config)
     den = drf.Denoiser(dit, w)
@@ -132,20 +181,40 @@ def main():
     }
 
     if not args.no_roofline:
-        # one more call with per-launch HIP events on the library's stream
-        den.profile_enable(True)
+        # call A: each predictor pass of the call bracketed as a whole (two events per pass, kernels undisturbed)
+        den.profile_enable(2)
+        step()
+        pf, po = den.profile_read(drf.PROF_PASS_FULL), den.profile_read(drf.PROF_PASS_OTHER)
+        # call B: every launch bracketed, per kernel family
+        den.profile_enable(1)
         step()
         fam = {k: den.profile_read(v) for k, v in (("gemm", drf.PROF_GEMM), ("attn", drf.PROF_ATTN),
                                                     ("elementwise", drf.PROF_ELEMWISE), ("update", drf.PROF_UPDATE))}
-        den.profile_enable(False)
+        den.profile_enable(0)
+        peaks = calibrate(torch, drf)
         gm = fam["gemm"]
-        ach = gm["work"] / (gm["ms"] * 1e-3) / 1e12 if gm["ms"] > 0 else 0.0
-        result["roofline"] = {"bound": "mfma", "kernel": "gemm_bf16_xl_kernel (all bf16 GEMM launches of one drf_sample call)",
-                              "achieved": ach, "peak": PEAK_BF16_TFLOPS, "unit": "TFLOP/s",
-                              "frac": ach / PEAK_BF16_TFLOPS,
-                              "traffic": GEMM_TRAFFIC_BYTES_PER_LAUNCH.get(args.config) if default_workload else None,
-                              "launches": gm["launches"], "avg_launch_us": gm["ms"] * 1e3 / max(gm["launches"], 1),
-                              "flops_per_launch": gm["work"] / max(gm["launches"], 1)}
+        g_ach = gm["work"] / (gm["ms"] * 1e-3) / 1e12 if gm["ms"] > 0 else 0.0
+        gemm = {"kernel": "gemm_bf16_xl_kernel (all bf16 GEMM launches of one drf_sample call)", "achieved": g_ach,
+                "frac": g_ach / PEAK_BF16_TFLOPS, "launches": gm["launches"],
+                "avg_launch_us": gm["ms"] * 1e3 / max(gm["launches"], 1), "flops_per_launch": gm["work"] / max(gm["launches"], 1),
+                "traffic": GEMM_TRAFFIC_BYTES_PER_LAUNCH.get(args.config) if default_workload else None}
+        dom = pf if pf["launches"] > 0 else po          # n = 1 conservative has no draft pass
+        ach = dom["work"] / (dom["ms"] * 1e-3) / 1e12 if dom["ms"] > 0 else 0.0
+        result["roofline"] = {"bound": "mfma",
+                              "kernel": "full draft pass: all kernels of one batched predictor pass over %d slots (%d per call)"
+                                        % (n * g * B if pf["launches"] > 0 else g * B, dom["launches"]),
+                              "achieved": ach, "peak": PEAK_BF16_TFLOPS, "unit": "TFLOP/s", "frac": ach / PEAK_BF16_TFLOPS,
+                              "traffic": PASS_TRAFFIC_BYTES.get(args.config) if default_workload else None,
+                              "avg_pass_ms": dom["ms"] / max(dom["launches"], 1),
+                              "flops_per_pass": dom["work"] / max(dom["launches"], 1),
+                              "peak_measured": peaks,
+                              "frac_of_measured_mfma_random": ach / peaks["mfma_bf16_random_operands_TFLOPs"],
+                              "gemm": gemm}
+        if pf["launches"] > 0 and po["launches"] > 0:
+            o_ach = po["work"] / (po["ms"] * 1e-3) / 1e12
+            result["roofline"]["other_passes"] = {"what": "stand-alone evaluations and cut-short blocks", "passes": po["launches"],
+                                                  "avg_pass_ms": po["ms"] / po["launches"], "achieved": o_ach,
+                                                  "frac": o_ach / PEAK_BF16_TFLOPS}
         result["families_ms"] = {k: round(v["ms"], 3) for k, v in fam.items()}
         at = fam["attn"]
         if at["ms"] > 0:
@@ -154,10 +223,11 @@ def main():
         if up["ms"] > 0:
             result["update_kernel"] = {"launches": up["launches"], "avg_launch_us": up["ms"] * 1e3 / up["launches"],
                                        "achieved_GBps": up["work"] / (up["ms"] * 1e-3) / 1e9}
+        result["update_kernel_fused_scaled"] = update_probe(10)
         # the update kernel at a size where bandwidth, not launch latency, decides: 4096 samples of this latent,
         # 4 drafts by skip transition (reads x and eps once, writes 4 fields)
         E = dit["in_ch"] * dit["lat_h"] * dit["lat_w"]
-        big = 4096
+        big = max(1, min(4096, (1 << 24) // E))
         xb = torch.randn((big, E), device="cuda")
         eb = torch.randn((big, E), device="cuda")
         ob = torch.empty((4, big, E), device="cuda")
@@ -190,27 +260,37 @@ def main():
 
     if not args.no_cpu_baseline:
         # the oracle as it stands, on a bounded sample of the same work: slot evaluations of the same DiT,
-        # one to size the sample, then as many more (in one call, at most 64) as bring it to ~12 s
+        # one to size the sample, then as many more (in one call, at most 64) as bring it to ~10 s.  The fp64
+        # build is the parity authority and the reported baseline; the fp32 build of the same text is timed
+        # beside it on a shorter sample.
         from oracle.ref import Oracle
-        orc = Oracle(64)
-        wd = orc.prepare_weights(w)
 
-        def timed(ns):
-            xs = I.latent_noise(dit, ns, args.config)
-            cs = I.conditioning(dit, ns, args.config)
-            ts = np.linspace(999, 0, ns).astype(np.int32)
-            t0 = time.perf_counter()
-            orc.dit_eps(dit, wd, xs, ts, cs)
-            return time.perf_counter() - t0
+        def timed_oracle(bits, budget):
+            orc = Oracle(bits)
+            wd = orc.prepare_weights(w)
 
-        n_done, ct = 1, timed(1)
-        more = min(64, int(12.0 / max(ct, 1e-3)))
-        if more >= 1 and ct < 10.0:
-            ct += timed(more)
-            n_done += more
-        result["cpu_baseline"] = {"value": n_done / ct, "unit": "eps-evals/s", "cores": orc.threads(), "kind": "oracle",
+            def timed(ns):
+                xs = I.latent_noise(dit, ns, args.config)
+                cs = I.conditioning(dit, ns, args.config)
+                ts = np.linspace(999, 0, ns).astype(np.int32)
+                t0 = time.perf_counter()
+                orc.dit_eps(dit, wd, xs, ts, cs)
+                return time.perf_counter() - t0
+
+            n_done, ct = 1, timed(1)
+            more = min(64, int(budget / max(ct, 1e-3)))
+            if more >= 1 and ct < budget:
+                ct += timed(more)
+                n_done += more
+            return n_done, ct, orc.threads()
+
+        n64, t64, cores = timed_oracle(64, 10.0)
+        n32, t32, _ = timed_oracle(32, 5.0)
+        result["cpu_baseline"] = {"value": n64 / t64, "unit": "eps-evals/s", "cores": cores, "kind": "oracle",
+                                  "precision": "fp64 build (the parity authority)",
                                   "sample": "%d slot evaluations of the same DiT (fp64 oracle, %.1f s); a full call is %d of them"
-                                            % (n_done, ct, evals)}
+                                            % (n64, t64, evals),
+                                  "fp32_build": {"value": n32 / t32, "sample": "%d slot evaluations, %.1f s" % (n32, t32)}}
     print(json.dumps(result))
 
 

@@ -22,7 +22,11 @@
  *   - Every call returns a drf_status; nothing throws or aborts across the ABI.
  *     drf_last_error() gives a thread-local message for the last failure.
  *     Asynchronous HIP faults surface at the caller's next synchronisation.
- *   - One denoiser handle may be used by one stream at a time.
+ *   - One denoiser handle may be used by one stream at a time, and only one handle per
+ *     process may have work in flight: a call on a handle while another handle's last call is
+ *     still running on a different stream returns DRF_EUNSUPPORTED (the kernels are sized for
+ *     sole occupancy of the GPU and the handles' work would interleave).  Handles used one
+ *     after the other on the same stream, or after a synchronisation, are fine.
  *
  * Indices.  Sampling indices s run S, S-1, ..., 1, 0 (the paper's t, with S the
  * paper's T).  DDIM / DDPM: the network is fed the training timestep tau_s = (s-1) *
@@ -170,13 +174,6 @@ drf_status drf_eps_batched(drf_denoiser* den, const float* x, const int32_t* t, 
                            int slots, float* eps_out, void* hip_stream);
 
 /*
- * Introspection for parity tests: run only the first n_blocks blocks (0 = embedding
- * only) and write the fp32 residual stream, DEVICE [slots][T][D], to resid_out.
- */
-drf_status drf_eps_trace(drf_denoiser* den, const float* x, const int32_t* t, const void* cond,
-                         int slots, int n_blocks, float* resid_out, void* hip_stream);
-
-/*
  * Skip transitions without a noise term.  DRF_DDIM with eta = 0 (Eq. ddim_skip_reverse,
  * zero variance; the draft line of Algorithm 1): for j < m,
  *   x_to[j] = sqrt(ab_to/ab_from) x_from + (sqrt(1-ab_to) - sqrt(ab_to/ab_from) sqrt(1-ab_from)) eps_from
@@ -270,35 +267,6 @@ drf_status drf_noise_count(const drf_sched_config* sched, drf_mode mode, int n, 
 #define DRF_PLAN_ROW 5
 drf_status drf_plan_build(const drf_sched_config* sched, drf_mode mode, int n, int32_t* rows, size_t cap,
                           size_t* n_rows);
-
-/*
- * Per-kernel-family timing with HIP events on the handle's stream, for roofline
- * reports.  While enabled, every launch of a family is bracketed by two events (this
- * adds a few microseconds per launch; leave it off when timing whole calls).
- * drf_profile_read synchronises the stream and returns, for family `which`
- * (DRF_PROF_*), the number of launches, their summed duration in milliseconds and
- * their summed algorithmic work (flops for GEMM/attention, bytes otherwise), then
- * clears the counters.
- */
-enum { DRF_PROF_GEMM = 0, DRF_PROF_ATTN = 1, DRF_PROF_ELEMWISE = 2, DRF_PROF_UPDATE = 3, DRF_PROF_FAMILIES = 4 };
-drf_status drf_profile_enable(drf_denoiser* den, int on);
-drf_status drf_profile_read(drf_denoiser* den, int which, long long* launches, double* ms, double* work);
-
-/*
- * Measurement hook: one launch of the library's bf16 GEMM on caller buffers,
- * out[M][N] (bf16) = A[M][K] (bf16) . W[N][K]^T (bf16) + bias[N] (fp32), all DEVICE.
- * variant 0 = the tile shape the forward pass would pick, > 0 forces one (for sweeps).
- * K % 64 == 0 and N % 4 == 0 are required.
- */
-drf_status drf_probe_gemm_bf16(const void* A, const void* W, int M, int N, int K, void* out_bf16, const float* bias,
-                               int variant, void* hip_stream);
-
-/*
- * Measurement hook: one launch of the bf16 self-attention kernel.  qkv: DEVICE bf16
- * [slots * tokens][3 * heads * head_dim] (q | k | v), out: DEVICE bf16 [slots * tokens][heads * head_dim].
- */
-drf_status drf_probe_attn_bf16(const void* qkv, void* out, int slots, int tokens, int heads, int head_dim,
-                               void* hip_stream);
 
 /* HOST, thread-local, valid until the next failing call on this thread. */
 const char* drf_last_error(void);

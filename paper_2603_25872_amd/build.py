@@ -8,7 +8,7 @@ HERE = os.path.dirname(os.path.abspath(__file__))
 CSRC = os.path.join(HERE, "csrc")
 OBJ = os.path.join(HERE, "_build")
 LIB = os.path.join(HERE, "libdrf.so")
-SOURCES = ["plan.cpp", "update.hip", "dit_kernels.hip", "gemm.hip", "attn.hip", "denoiser.hip"]
+SOURCES = ["plan.cpp", "update.hip", "dit_kernels.hip", "gemm.hip", "attn.hip", "denoiser.hip", "calibrate.hip"]
 FLAGS = ["-x", "hip", "--offload-arch=gfx950", "-O3", "-std=c++17", "-fPIC", "-Wall", "-Wno-unused-function",
          "-Xclang", "-target-feature", "-Xclang", "-packed-fp32-ops"]
 

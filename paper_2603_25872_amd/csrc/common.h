@@ -121,7 +121,9 @@ void make_fast_div(int d, uint32_t* magic, int* shift);
 // Fills rows_per_slot and its division constants (exact for 0 <= m < 2^31).
 void set_rows_per_slot(Epilogue* e, int rows_per_slot);
 // C[M][N] = A[M][K] . W[N][K]^T, then the epilogue.  bf16: K % 64 == 0.
-drf_status launch_gemm_bf16(const bf16_t* A, const bf16_t* W, int M, int N, int K, const Epilogue& e, hipStream_t st);
+// variant 0: the tile shape is chosen from the problem size; > 0 forces one (measurement and tile tests).
+drf_status launch_gemm_bf16(const bf16_t* A, const bf16_t* W, int M, int N, int K, const Epilogue& e, hipStream_t st,
+                            int variant = 0);
 drf_status launch_gemm_f32(const float* A, const float* W, int M, int N, int K, const Epilogue& e, hipStream_t st);
 
 struct AttnArgs {

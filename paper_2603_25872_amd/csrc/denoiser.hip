@@ -1,8 +1,10 @@
 // The denoiser handle, the batched DiT forward and the draft-and-refine loop.
 #include <cmath>
 #include <cstring>
+#include <mutex>
 
 #include "common.h"
+#include "../../include/drf_measure.h"
 
 using namespace drf;
 
@@ -19,8 +21,17 @@ struct LinearW {
 
 struct BlockW { LinearW qkv, proj, xq, xkv, xo, fc1, fc2; };
 
+// Device buffers of one batched pass beyond the caller's inputs and outputs: activations, the
+// conditioning front-end's rows and the modulation table, the K/V of a text context.  Either owned by
+// the handle (grown on demand) or handed in by the caller of forward().
+struct Workspace {
+    float *resid = nullptr, *mod = nullptr, *cact32 = nullptr, *cscratch = nullptr;
+    void *hbuf = nullptr, *qkv = nullptr, *mid = nullptr, *ybuf = nullptr, *ybuf2 = nullptr, *cact = nullptr;
+    void *xkv = nullptr, *ctx_act = nullptr;    // cross-attention K/V cache [L][rows][ctx_len][2D] and its staging
+};
+
 struct Prof {
-    bool on = false;
+    int on = 0;                     // 0 off | 1 per launch | 2 per predictor pass of drf_sample
     std::vector<hipEvent_t> pool;
     struct Rec { int fam; size_t e0, e1; double work; };
     std::vector<Rec> recs;
@@ -42,17 +53,18 @@ struct drf_denoiser {
     LinearW ada;                    // all blocks' adaLN projections and the final one, stacked [n_mod][D]
     std::vector<BlockW> blk;
     float* pos = nullptr;           // [T][D]
-    // workspace
-    int cap_slots = 0, cap_cond_rows = 0;
-    float *resid = nullptr, *mod = nullptr, *cact32 = nullptr, *cscratch = nullptr;
-    void *hbuf = nullptr, *qkv = nullptr, *mid = nullptr, *ybuf = nullptr, *ybuf2 = nullptr, *cact = nullptr;
-    // cross-attention K/V cache [L][rows][ctx_len][2D] and its staging
-    void* xkv = nullptr; void* ctx_act = nullptr; int cap_ctx_rows = 0;
+    // workspace (owned)
+    Workspace ws;
+    int cap_slots = 0, cap_cond_rows = 0, cap_ctx_rows = 0;
     // sampler buffers
-    int cap_sample_n = 0, cap_sample_field = 0, cap_sample_g = 0;
+    int cap_sample_n = 0, cap_sample_g = 0;
+    size_t cap_sample_field = 0;
     float *drafts = nullptr, *epsbuf = nullptr, *anchor = nullptr;
     void* cond_cat = nullptr; size_t cond_cat_bytes = 0;
     Prof prof;
+    // the stream of this handle's last call and an event recorded behind that call's work
+    hipStream_t last_stream = nullptr;
+    hipEvent_t done = nullptr;
 };
 
 namespace {
@@ -69,8 +81,11 @@ drf_status dev_alloc(drf_denoiser* d, void** p, size_t bytes)
     return DRF_OK;
 }
 
-void dev_free(drf_denoiser* d, void* p)
+// Frees *pp and clears it, so that a later failure never leaves a freed address behind.
+template <typename T> void dev_free(drf_denoiser* d, T** pp)
 {
+    void* p = (void*)*pp;
+    *pp = nullptr;
     if (!p) return;
     for (size_t i = 0; i < d->allocs.size(); ++i)
         if (d->allocs[i] == p) { d->allocs.erase(d->allocs.begin() + (long)i); break; }
@@ -129,7 +144,8 @@ struct ProfScope {
     ProfScope(drf_denoiser* d_, hipStream_t st_, int fam, double work) : d(d_), st(st_)
     {
         Prof& p = d->prof;
-        if (!p.on) return;
+        const bool pass_family = fam == DRF_PROF_PASS_FULL || fam == DRF_PROF_PASS_OTHER;
+        if (p.on == 0 || (p.on == 2) != pass_family) return;
         while (p.pool.size() < p.used + 2) {
             hipEvent_t ev;
             if (hipEventCreate(&ev) != hipSuccess) return;
@@ -144,22 +160,41 @@ struct ProfScope {
     ~ProfScope() { if (live) (void)hipEventRecord(d->prof.pool[d->prof.recs[rec].e1], st); }
 };
 
-// Activation buffers for `slots` samples per pass.
+// Sizes (bytes) of the Workspace members for a pass of `slots` slots, `cond_rows` conditioning rows and
+// `ctx_rows` distinct text contexts: the one table every workspace layout is built from.
+struct WorkspaceBytes { size_t resid, hbuf, qkv, mid, ybuf, ybuf2, mod, cact32, cscratch, cact, xkv, ctx_act; };
+WorkspaceBytes workspace_bytes(const drf_denoiser* d, size_t slots, size_t cond_rows, size_t ctx_rows)
+{
+    const size_t M = slots * d->dm.T, D = (size_t)d->dm.D, act = d->bf16 ? 2 : 4;
+    WorkspaceBytes b{};
+    b.resid = M * D * 4; b.hbuf = M * D * act; b.qkv = M * 3 * D * act; b.mid = M * (size_t)d->dm.R * D * act;
+    b.ybuf = M * D * act; b.ybuf2 = d->bf16 ? M * D * act : 0;
+    b.mod = cond_rows * d->n_mod * 4; b.cact32 = cond_rows * D * 4; b.cscratch = cond_rows * (kTFreq + 3 * D) * 4;
+    b.cact = cond_rows * D * act;
+    if (d->cfg.cond == DRF_COND_TEXT) {
+        const size_t rl = ctx_rows * d->cfg.ctx_len;
+        b.xkv = (size_t)d->dm.L * rl * 2 * D * act; b.ctx_act = rl * d->cfg.cond_dim * act;
+    }
+    return b;
+}
+
+// Activation buffers for `slots` samples per pass.  On a failed allocation every member is either a
+// live buffer or NULL and the capacity is 0, so the handle stays usable.
 drf_status ensure_workspace(drf_denoiser* d, int slots, hipStream_t st)
 {
     if (slots <= d->cap_slots) return DRF_OK;
     DRF_HIP(hipStreamSynchronize(st));
-    void* olds[] = { d->resid, d->hbuf, d->qkv, d->mid, d->ybuf, d->ybuf2 };
-    for (void* p : olds) dev_free(d, p);
+    Workspace& w = d->ws;
     d->cap_slots = 0;
-    const size_t M = (size_t)slots * d->dm.T, D = (size_t)d->dm.D, act = d->bf16 ? 2 : 4;
+    dev_free(d, &w.resid); dev_free(d, &w.hbuf); dev_free(d, &w.qkv); dev_free(d, &w.mid); dev_free(d, &w.ybuf); dev_free(d, &w.ybuf2);
+    const WorkspaceBytes b = workspace_bytes(d, (size_t)slots, 0, 0);
     drf_status rc;
-    if ((rc = dev_alloc(d, (void**)&d->resid, M * D * 4)) != DRF_OK) return rc;
-    if ((rc = dev_alloc(d, &d->hbuf, M * D * act)) != DRF_OK) return rc;
-    if ((rc = dev_alloc(d, &d->qkv, M * 3 * D * act)) != DRF_OK) return rc;
-    if ((rc = dev_alloc(d, &d->mid, M * (size_t)d->dm.R * D * act)) != DRF_OK) return rc;
-    if ((rc = dev_alloc(d, &d->ybuf, M * D * act)) != DRF_OK) return rc;
-    if ((rc = dev_alloc(d, &d->ybuf2, d->bf16 ? M * D * act : 0)) != DRF_OK) return rc;
+    if ((rc = dev_alloc(d, (void**)&w.resid, b.resid)) != DRF_OK) return rc;
+    if ((rc = dev_alloc(d, &w.hbuf, b.hbuf)) != DRF_OK) return rc;
+    if ((rc = dev_alloc(d, &w.qkv, b.qkv)) != DRF_OK) return rc;
+    if ((rc = dev_alloc(d, &w.mid, b.mid)) != DRF_OK) return rc;
+    if ((rc = dev_alloc(d, &w.ybuf, b.ybuf)) != DRF_OK) return rc;
+    if ((rc = dev_alloc(d, &w.ybuf2, b.ybuf2)) != DRF_OK) return rc;
     d->cap_slots = slots;
     return DRF_OK;
 }
@@ -169,15 +204,15 @@ drf_status ensure_cond(drf_denoiser* d, int rows, hipStream_t st)
 {
     if (rows <= d->cap_cond_rows) return DRF_OK;
     DRF_HIP(hipStreamSynchronize(st));
-    void* olds[] = { d->mod, d->cact32, d->cscratch, d->cact };
-    for (void* p : olds) dev_free(d, p);
+    Workspace& w = d->ws;
     d->cap_cond_rows = 0;
-    const size_t D = (size_t)d->dm.D, act = d->bf16 ? 2 : 4;
+    dev_free(d, &w.mod); dev_free(d, &w.cact32); dev_free(d, &w.cscratch); dev_free(d, &w.cact);
+    const WorkspaceBytes b = workspace_bytes(d, 0, (size_t)rows, 0);
     drf_status rc;
-    if ((rc = dev_alloc(d, (void**)&d->mod, (size_t)rows * d->n_mod * 4)) != DRF_OK) return rc;
-    if ((rc = dev_alloc(d, (void**)&d->cact32, (size_t)rows * D * 4)) != DRF_OK) return rc;
-    if ((rc = dev_alloc(d, (void**)&d->cscratch, (size_t)rows * (kTFreq + 3 * D) * 4)) != DRF_OK) return rc;
-    if ((rc = dev_alloc(d, &d->cact, (size_t)rows * D * act)) != DRF_OK) return rc;
+    if ((rc = dev_alloc(d, (void**)&w.mod, b.mod)) != DRF_OK) return rc;
+    if ((rc = dev_alloc(d, (void**)&w.cact32, b.cact32)) != DRF_OK) return rc;
+    if ((rc = dev_alloc(d, (void**)&w.cscratch, b.cscratch)) != DRF_OK) return rc;
+    if ((rc = dev_alloc(d, &w.cact, b.cact)) != DRF_OK) return rc;
     d->cap_cond_rows = rows;
     return DRF_OK;
 }
@@ -186,12 +221,13 @@ drf_status ensure_ctx(drf_denoiser* d, int rows, hipStream_t st)
 {
     if (d->cfg.cond != DRF_COND_TEXT || rows <= d->cap_ctx_rows) return DRF_OK;
     DRF_HIP(hipStreamSynchronize(st));
-    dev_free(d, d->xkv); dev_free(d, d->ctx_act);
+    Workspace& w = d->ws;
     d->cap_ctx_rows = 0;
-    const size_t act = d->bf16 ? 2 : 4, rl = (size_t)rows * d->cfg.ctx_len;
+    dev_free(d, &w.xkv); dev_free(d, &w.ctx_act);
+    const WorkspaceBytes b = workspace_bytes(d, 0, 0, (size_t)rows);
     drf_status rc;
-    if ((rc = dev_alloc(d, &d->xkv, (size_t)d->dm.L * rl * 2 * d->dm.D * act)) != DRF_OK) return rc;
-    if ((rc = dev_alloc(d, &d->ctx_act, rl * d->cfg.cond_dim * act)) != DRF_OK) return rc;
+    if ((rc = dev_alloc(d, &w.xkv, b.xkv)) != DRF_OK) return rc;
+    if ((rc = dev_alloc(d, &w.ctx_act, b.ctx_act)) != DRF_OK) return rc;
     d->cap_ctx_rows = rows;
     return DRF_OK;
 }
@@ -247,19 +283,18 @@ Epilogue with_warm(Epilogue e, const LinearW* next)
 }
 
 // K/V of the text context for every block: xkv[l][row][ctx][2D] = Linear(ctx[row]).
-drf_status compute_ctx_kv(drf_denoiser* d, const float* ctx, int rows, hipStream_t st)
+drf_status compute_ctx_kv(drf_denoiser* d, const Workspace& ws, const float* ctx, int rows, hipStream_t st)
 {
-    drf_status rc = ensure_ctx(d, rows, st);
-    if (rc != DRF_OK) return rc;
+    drf_status rc;
     const size_t rl = (size_t)rows * d->cfg.ctx_len, act = d->bf16 ? 2 : 4;
     const void* A = ctx;
     if (d->bf16) {
         ProfScope ps(d, st, DRF_PROF_ELEMWISE, 6.0 * rl * d->cfg.cond_dim);
-        if ((rc = launch_f32_to_bf16(ctx, (bf16_t*)d->ctx_act, rl * d->cfg.cond_dim, st)) != DRF_OK) return rc;
-        A = d->ctx_act;
+        if ((rc = launch_f32_to_bf16(ctx, (bf16_t*)ws.ctx_act, rl * d->cfg.cond_dim, st)) != DRF_OK) return rc;
+        A = ws.ctx_act;
     }
     for (int l = 0; l < d->dm.L; ++l) {
-        void* out = (char*)d->xkv + (size_t)l * rl * 2 * d->dm.D * act;
+        void* out = (char*)ws.xkv + (size_t)l * rl * 2 * d->dm.D * act;
         if ((rc = gemm(d, A, d->blk[l].xkv, (int)rl, epi_store(out, 2 * d->dm.D, !d->bf16), st)) != DRF_OK) return rc;
     }
     return DRF_OK;
@@ -268,8 +303,8 @@ drf_status compute_ctx_kv(drf_denoiser* d, const float* ctx, int rows, hipStream
 // Conditioning of `rows` slot rows (they need not belong to one pass): c = MLP(femb(tau)) + cond
 // embedding per row, then every block's shift / scale / gate and the final layer's in ONE GEMM
 // against the stacked adaLN projections.  Row r of the result is mod_out[r][0 .. n_mod).
-drf_status conditioning(drf_denoiser* d, const SlotMap& map, const void* cond, int rows, int row0, float* mod_out,
-                        hipStream_t st)
+drf_status conditioning(drf_denoiser* d, const Workspace& ws, const SlotMap& map, const void* cond, int rows, int row0,
+                        float* mod_out, hipStream_t st)
 {
     const int D = d->dm.D;
     drf_status rc;
@@ -277,9 +312,9 @@ drf_status conditioning(drf_denoiser* d, const SlotMap& map, const void* cond, i
     ca.t_w1 = d->t_w1; ca.t_b1 = d->t_b1; ca.t_w2 = d->t_w2; ca.t_b2 = d->t_b2; ca.c_w = d->c_w; ca.c_b = d->c_b;
     ca.table = d->table; ca.cond = cond; ca.cond_kind = d->cfg.cond; ca.cond_dim = d->cfg.cond_dim; ca.D = D;
     ca.slots = rows; ca.map = map;
-    ca.act_f32 = d->cact32 + (size_t)row0 * D;
-    ca.act_bf16 = d->bf16 ? (bf16_t*)d->cact + (size_t)row0 * D : nullptr;
-    ca.scratch = d->cscratch + (size_t)row0 * (kTFreq + 3 * D);
+    ca.act_f32 = ws.cact32 + (size_t)row0 * D;
+    ca.act_bf16 = d->bf16 ? (bf16_t*)ws.cact + (size_t)row0 * D : nullptr;
+    ca.scratch = ws.cscratch + (size_t)row0 * (kTFreq + 3 * D);
     {
         ProfScope ps(d, st, DRF_PROF_ELEMWISE, 4.0 * rows * ((double)kTFreq * D + (double)D * D));
         if ((rc = launch_cond_embed(ca, st)) != DRF_OK) return rc;
@@ -288,18 +323,18 @@ drf_status conditioning(drf_denoiser* d, const SlotMap& map, const void* cond, i
     return gemm(d, A, d->ada, rows, epi_store(mod_out, d->n_mod, true), st);
 }
 
-// The batched forward.  mod: this pass's rows of the modulation table (see conditioning()).
-drf_status forward(drf_denoiser* d, const float* x, const SlotMap& map, const float* mod, int slots, int n_blocks,
-                   float* eps_out, float* resid_out, hipStream_t st)
+// The batched forward on the buffers of `ws` (sized for at least `slots` slots by the caller).
+// mod: this pass's rows of the modulation table (see conditioning()).
+drf_status forward(drf_denoiser* d, const Workspace& ws, const float* x, const SlotMap& map, const float* mod, int slots,
+                   int n_blocks, float* eps_out, float* resid_out, hipStream_t st)
 {
     const DitDims& dm = d->dm;
     const int D = dm.D, M = slots * dm.T, nm = d->n_mod;
     const bool f32 = !d->bf16;
     drf_status rc;
-    if ((rc = ensure_workspace(d, slots, st)) != DRF_OK) return rc;
     {
         ProfScope ps(d, st, DRF_PROF_ELEMWISE, (double)M * D * 8.0 + (double)M * dm.P * 4.0);
-        if ((rc = launch_patch_embed(x, map, d->patch_w, d->patch_b, d->pos, dm, slots, d->resid, st)) != DRF_OK) return rc;
+        if ((rc = launch_patch_embed(x, map, d->patch_w, d->patch_b, d->pos, dm, slots, ws.resid, st)) != DRF_OK) return rc;
     }
     const double ln_bytes = (double)M * D * (4.0 + (f32 ? 4.0 : 2.0));
     const size_t act = f32 ? 4 : 2;
@@ -320,7 +355,7 @@ drf_status forward(drf_denoiser* d, const float* x, const SlotMap& map, const fl
     auto ln = [&](const float* shift, const float* scale, int mod_ld, bool store) -> drf_status {
         const int n_add = (pend1 ? 1 : 0) + (pend2 ? 1 : 0);
         ProfScope ps(d, st, DRF_PROF_ELEMWISE, ln_bytes + (double)M * D * (2.0 * n_add + (n_add && store ? 4.0 : 0.0)));
-        const drf_status r = launch_ln_modulate(d->resid, pend1, pend2, store, shift, scale, mod_ld, dm.T, M, D, d->hbuf, f32, st);
+        const drf_status r = launch_ln_modulate(ws.resid, pend1, pend2, store, shift, scale, mod_ld, dm.T, M, D, ws.hbuf, f32, st);
         if (store) pend1 = pend2 = nullptr;
         return r;
     };
@@ -330,17 +365,17 @@ drf_status forward(drf_denoiser* d, const float* x, const SlotMap& map, const fl
         if ((rc = ln(mrow, mrow + D, nm, true)) != DRF_OK) return rc;
         // bf16: q | k | v are stored head-major ([slot][head][token][d] planes) so that attention reads
         // whole contiguous tiles; fp32: packed rows
-        if ((rc = gemm(d, d->hbuf, b.qkv, M, f32 ? epi_store(d->qkv, 3 * D, true) : with_warm(epi_heads(d->qkv, M, dm), &b.proj), st)) != DRF_OK) return rc;
+        if ((rc = gemm(d, ws.hbuf, b.qkv, M, f32 ? epi_store(ws.qkv, 3 * D, true) : with_warm(epi_heads(ws.qkv, M, dm), &b.proj), st)) != DRF_OK) return rc;
         {
             AttnArgs aa{};
-            aa.q = d->qkv; aa.out = d->hbuf; aa.ldo = D; aa.Nq = dm.T; aa.Nk = dm.T; aa.heads = dm.heads; aa.d = dm.d;
+            aa.q = ws.qkv; aa.out = ws.hbuf; aa.ldo = D; aa.Nq = dm.T; aa.Nk = dm.T; aa.heads = dm.heads; aa.d = dm.d;
             aa.slots = slots; aa.kv_mod = 0;
             if (f32) {
-                aa.k = (char*)d->qkv + (size_t)D * act; aa.v = (char*)d->qkv + (size_t)2 * D * act;
+                aa.k = (char*)ws.qkv + (size_t)D * act; aa.v = (char*)ws.qkv + (size_t)2 * D * act;
                 aa.ldq = aa.ldk = 3 * D;
                 aa.q_slot_stride = aa.kv_batch_stride = (size_t)dm.T * 3 * D; aa.q_head_stride = aa.kv_head_stride = dm.d;
             } else {
-                aa.k = (char*)d->qkv + (size_t)M * D * act; aa.v = (char*)d->qkv + (size_t)2 * M * D * act;
+                aa.k = (char*)ws.qkv + (size_t)M * D * act; aa.v = (char*)ws.qkv + (size_t)2 * M * D * act;
                 aa.ldq = aa.ldk = dm.d;
                 aa.q_slot_stride = aa.kv_batch_stride = (size_t)dm.T * D; aa.q_head_stride = aa.kv_head_stride = (size_t)dm.T * dm.d;
             }
@@ -348,18 +383,18 @@ drf_status forward(drf_denoiser* d, const float* x, const SlotMap& map, const fl
             if ((rc = f32 ? launch_attn_f32(aa, st) : launch_attn_bf16(aa, st)) != DRF_OK) return rc;
         }
         if (f32) {
-            if ((rc = gemm(d, d->hbuf, b.proj, M, epi_resid(d->resid, D, mrow + 2 * D, nm, dm.T), st)) != DRF_OK) return rc;
+            if ((rc = gemm(d, ws.hbuf, b.proj, M, epi_resid(ws.resid, D, mrow + 2 * D, nm, dm.T), st)) != DRF_OK) return rc;
         } else {
-            if ((rc = gemm(d, d->hbuf, b.proj, M, with_warm(epi_gated(d->ybuf, D, mrow + 2 * D, nm, dm.T), text ? nullptr : &b.fc1), st)) != DRF_OK) return rc;
-            pend1 = (const bf16_t*)d->ybuf;
+            if ((rc = gemm(d, ws.hbuf, b.proj, M, with_warm(epi_gated(ws.ybuf, D, mrow + 2 * D, nm, dm.T), text ? nullptr : &b.fc1), st)) != DRF_OK) return rc;
+            pend1 = (const bf16_t*)ws.ybuf;
         }
         if (d->cfg.cond == DRF_COND_TEXT) {
             const int ctx_rows = map.cond_mod ? map.cond_mod : slots;
             if ((rc = ln(nullptr, nullptr, 0, true)) != DRF_OK) return rc;
-            if ((rc = gemm(d, d->hbuf, b.xq, M, epi_store(d->qkv, D, f32), st)) != DRF_OK) return rc;
-            const char* kv = (const char*)d->xkv + (size_t)l * ctx_rows * d->cfg.ctx_len * 2 * D * act;
+            if ((rc = gemm(d, ws.hbuf, b.xq, M, epi_store(ws.qkv, D, f32), st)) != DRF_OK) return rc;
+            const char* kv = (const char*)ws.xkv + (size_t)l * ctx_rows * d->cfg.ctx_len * 2 * D * act;
             AttnArgs aa{};
-            aa.q = d->qkv; aa.ldq = D; aa.k = kv; aa.v = kv + (size_t)D * act; aa.ldk = 2 * D; aa.out = d->hbuf; aa.ldo = D;
+            aa.q = ws.qkv; aa.ldq = D; aa.k = kv; aa.v = kv + (size_t)D * act; aa.ldk = 2 * D; aa.out = ws.hbuf; aa.ldo = D;
             aa.q_slot_stride = (size_t)dm.T * D; aa.q_head_stride = dm.d;
             aa.kv_batch_stride = (size_t)d->cfg.ctx_len * 2 * D; aa.kv_head_stride = dm.d;
             aa.Nq = dm.T; aa.Nk = d->cfg.ctx_len; aa.heads = dm.heads; aa.d = dm.d; aa.slots = slots; aa.kv_mod = map.cond_mod;
@@ -367,27 +402,37 @@ drf_status forward(drf_denoiser* d, const float* x, const SlotMap& map, const fl
                 ProfScope ps(d, st, DRF_PROF_ATTN, 4.0 * slots * dm.heads * (double)dm.T * d->cfg.ctx_len * dm.d);
                 if ((rc = f32 ? launch_attn_f32(aa, st) : launch_attn_bf16(aa, st)) != DRF_OK) return rc;
             }
-            if ((rc = gemm(d, d->hbuf, b.xo, M, epi_resid(d->resid, D, nullptr, 0, dm.T), st)) != DRF_OK) return rc;
+            if ((rc = gemm(d, ws.hbuf, b.xo, M, epi_resid(ws.resid, D, nullptr, 0, dm.T), st)) != DRF_OK) return rc;
         }
         const bool last = l == n_blocks - 1;
         if ((rc = ln(mrow + 3 * D, mrow + 4 * D, nm, f32 || last)) != DRF_OK) return rc;
-        if ((rc = gemm(d, d->hbuf, b.fc1, M, with_warm(epi_store(d->mid, dm.R * D, f32, true), f32 ? nullptr : &b.fc2), st)) != DRF_OK) return rc;
+        if ((rc = gemm(d, ws.hbuf, b.fc1, M, with_warm(epi_store(ws.mid, dm.R * D, f32, true), f32 ? nullptr : &b.fc2), st)) != DRF_OK) return rc;
         if (f32 || last) {
-            if ((rc = gemm(d, d->mid, b.fc2, M, epi_resid(d->resid, D, mrow + 5 * D, nm, dm.T), st)) != DRF_OK) return rc;
+            if ((rc = gemm(d, ws.mid, b.fc2, M, epi_resid(ws.resid, D, mrow + 5 * D, nm, dm.T), st)) != DRF_OK) return rc;
         } else {
             // the attention output may still be pending in ybuf: the MLP output goes to the second buffer
-            void* yo = pend1 ? d->ybuf2 : d->ybuf;
-            if ((rc = gemm(d, d->mid, b.fc2, M, with_warm(epi_gated(yo, D, mrow + 5 * D, nm, dm.T), &d->blk[l + 1].qkv), st)) != DRF_OK) return rc;
+            void* yo = pend1 ? ws.ybuf2 : ws.ybuf;
+            if ((rc = gemm(d, ws.mid, b.fc2, M, with_warm(epi_gated(yo, D, mrow + 5 * D, nm, dm.T), &d->blk[l + 1].qkv), st)) != DRF_OK) return rc;
             (pend1 ? pend2 : pend1) = (const bf16_t*)yo;
         }
     }
     if (resid_out) {
-        DRF_HIP(hipMemcpyAsync(resid_out, d->resid, (size_t)M * D * 4, hipMemcpyDeviceToDevice, st));
+        DRF_HIP(hipMemcpyAsync(resid_out, ws.resid, (size_t)M * D * 4, hipMemcpyDeviceToDevice, st));
         return DRF_OK;
     }
     const float* fm = mod + (size_t)dm.L * 6 * D;           // final shift | scale
     ProfScope ps(d, st, DRF_PROF_ELEMWISE, (double)M * D * 4.0 + (double)M * dm.P * 4.0);
-    return launch_final(d->resid, fm, fm + D, nm, d->fin_w, d->fin_b, dm, slots, eps_out, st);
+    return launch_final(ws.resid, fm, fm + D, nm, d->fin_w, d->fin_b, dm, slots, eps_out, st);
+}
+
+// Algorithmic flops of one slot evaluation: 2 M N K of every Linear of the blocks and of the patch / final
+// projections, 4 T^2 D per self-attention (and 4 T ctx_len D per cross-attention), unpadded head width.
+double slot_eval_flops(const drf_denoiser* d)
+{
+    const double D = d->dm.D, T = d->dm.T, R = d->dm.R, P = d->dm.P;
+    double per = 2 * T * D * 3 * D + 2 * T * D * D + 2 * 2 * T * D * R * D + 4 * T * T * D;
+    if (d->cfg.cond == DRF_COND_TEXT) per += 2 * 2 * T * D * D + 4 * T * (double)d->cfg.ctx_len * D;
+    return d->dm.L * per + 2 * 2 * T * D * P;
 }
 
 SlotMap identity_map(const int32_t* t)
@@ -395,6 +440,46 @@ SlotMap identity_map(const int32_t* t)
     SlotMap m{};
     m.t_dev = t; m.group = 1; m.x_group = 1; m.x_batch = 1; m.cond_mod = 0;
     return m;
+}
+
+// ---- one handle in flight -----------------------------------------------------------------------
+// Work of two handles overlapping on one GPU from different streams is not supported: the kernels
+// are sized for sole occupancy of the chip.  Every enqueueing call first checks that the handle that enqueued last has finished, or
+// was used on the same stream (stream order then serialises the two), and records an event behind
+// its own work.  Skipped while the stream is being captured (an event recorded there cannot be queried).
+std::mutex g_flight_mu;
+drf_denoiser* g_last_handle = nullptr;
+
+bool capturing(hipStream_t st)
+{
+    hipStreamCaptureStatus cs = hipStreamCaptureStatusNone;
+    if (hipStreamIsCapturing(st, &cs) != hipSuccess) { (void)hipGetLastError(); return false; }
+    return cs != hipStreamCaptureStatusNone;
+}
+
+drf_status claim_device(drf_denoiser* d, hipStream_t st)
+{
+    if (capturing(st)) return DRF_OK;
+    std::lock_guard<std::mutex> lk(g_flight_mu);
+    drf_denoiser* o = g_last_handle;
+    if (o && o != d && o->last_stream != st && o->done) {
+        const hipError_t q = hipEventQuery(o->done);
+        if (q == hipErrorNotReady)
+            DRF_FAIL(DRF_EUNSUPPORTED, "another denoiser handle still has work in flight on a different stream; "
+                                       "synchronise that stream first (one handle in flight per process)");
+        if (q != hipSuccess) (void)hipGetLastError();
+    }
+    return DRF_OK;
+}
+
+drf_status mark_in_flight(drf_denoiser* d, hipStream_t st)
+{
+    if (capturing(st)) return DRF_OK;
+    std::lock_guard<std::mutex> lk(g_flight_mu);
+    if (d->done) DRF_HIP(hipEventRecord(d->done, st));
+    d->last_stream = st;
+    g_last_handle = d;
+    return DRF_OK;
 }
 
 drf_status eps_common(drf_denoiser* den, const float* x, const int32_t* t, const void* cond, int slots, int n_blocks,
@@ -406,11 +491,16 @@ drf_status eps_common(drf_denoiser* den, const float* x, const int32_t* t, const
     if (!x || !t || !cond || (!eps_out && !resid_out)) DRF_FAIL(DRF_EINVAL, "NULL buffer");
     if ((size_t)slots * den->dm.T > (size_t)1 << 30) DRF_FAIL(DRF_EINVAL, "slots * tokens too large");
     drf_status rc;
-    if (den->cfg.cond == DRF_COND_TEXT && (rc = compute_ctx_kv(den, (const float*)cond, slots, st)) != DRF_OK) return rc;
-    const SlotMap map = identity_map(t);
+    if ((rc = claim_device(den, st)) != DRF_OK) return rc;
+    if ((rc = ensure_workspace(den, slots, st)) != DRF_OK) return rc;
     if ((rc = ensure_cond(den, slots, st)) != DRF_OK) return rc;
-    if ((rc = conditioning(den, map, cond, slots, 0, den->mod, st)) != DRF_OK) return rc;
-    return forward(den, x, map, den->mod, slots, n_blocks, eps_out, resid_out, st);
+    if ((rc = ensure_ctx(den, slots, st)) != DRF_OK) return rc;
+    const Workspace& ws = den->ws;
+    if (den->cfg.cond == DRF_COND_TEXT && (rc = compute_ctx_kv(den, ws, (const float*)cond, slots, st)) != DRF_OK) return rc;
+    const SlotMap map = identity_map(t);
+    if ((rc = conditioning(den, ws, map, cond, slots, 0, ws.mod, st)) != DRF_OK) return rc;
+    if ((rc = forward(den, ws, x, map, ws.mod, slots, n_blocks, eps_out, resid_out, st)) != DRF_OK) return rc;
+    return mark_in_flight(den, st);
 }
 
 }  // namespace
@@ -535,9 +625,10 @@ extern "C" drf_status drf_denoiser_create(const drf_dit_config* cfg, const float
     if (hipStreamSynchronize(st) != hipSuccess) { set_error("create: stream synchronise failed"); return fail(DRF_EHIP); }
     if (d->bf16) {
         // the fp32 copies of the big matrices are no longer needed; keep params32 (small tensors point into it)
-        dev_free(d, ada_w);
+        dev_free(d, &ada_w);
         d->ada.w32 = nullptr;
     }
+    if (hipEventCreateWithFlags(&d->done, hipEventDisableTiming) != hipSuccess) { set_error("create: event creation failed"); return fail(DRF_EHIP); }
     *out = d;
     return DRF_OK;
 }
@@ -545,7 +636,15 @@ extern "C" drf_status drf_denoiser_create(const drf_dit_config* cfg, const float
 extern "C" void drf_denoiser_destroy(drf_denoiser* den)
 {
     if (!den) return;
+    {
+        std::lock_guard<std::mutex> lk(g_flight_mu);
+        if (g_last_handle == den) {
+            // its work may still be running: hipFree below waits for the device, after which no other handle can collide with it
+            g_last_handle = nullptr;
+        }
+    }
     for (void* p : den->allocs) (void)hipFree(p);
+    if (den->done) (void)hipEventDestroy(den->done);
     for (hipEvent_t ev : den->prof.pool) (void)hipEventDestroy(ev);
     delete den;
 }
@@ -553,8 +652,9 @@ extern "C" void drf_denoiser_destroy(drf_denoiser* den)
 extern "C" drf_status drf_denoiser_reserve(drf_denoiser* den, int max_slots)
 {
     if (!den || max_slots < 0) DRF_FAIL(DRF_EINVAL, "bad argument");
-    drf_status rc = ensure_workspace(den, max_slots, nullptr);
-    return rc != DRF_OK ? rc : ensure_cond(den, max_slots, nullptr);
+    drf_status rc = ensure_workspace(den, max_slots, den->last_stream);
+    if (rc == DRF_OK) rc = ensure_cond(den, max_slots, den->last_stream);
+    return rc != DRF_OK ? rc : ensure_ctx(den, max_slots, den->last_stream);
 }
 
 extern "C" drf_status drf_eps_batched(drf_denoiser* den, const float* x, const int32_t* t, const void* cond, int slots,
@@ -621,14 +721,15 @@ extern "C" drf_status drf_sample_noise(drf_denoiser* den, const drf_sched_config
     if ((size_t)n * gB * dm.T > (size_t)1 << 30) DRF_FAIL(DRF_EINVAL, "n * batch * tokens too large");
 
     // buffers: drafts [n][B][E], noises [n][g][B][E], anchor [B][E], conditioning rows [g*B]
-    if (n > den->cap_sample_n || (size_t)den->cap_sample_field < field || g > den->cap_sample_g) {
+    if ((rc = claim_device(den, st)) != DRF_OK) return rc;
+    if (n > den->cap_sample_n || den->cap_sample_field < field || g > den->cap_sample_g) {
         DRF_HIP(hipStreamSynchronize(st));
-        dev_free(den, den->drafts); dev_free(den, den->epsbuf); dev_free(den, den->anchor);
-        den->cap_sample_n = 0;
+        den->cap_sample_n = 0; den->cap_sample_field = 0; den->cap_sample_g = 0;
+        dev_free(den, &den->drafts); dev_free(den, &den->epsbuf); dev_free(den, &den->anchor);
         if ((rc = dev_alloc(den, (void**)&den->drafts, (size_t)n * field * 4)) != DRF_OK) return rc;
         if ((rc = dev_alloc(den, (void**)&den->epsbuf, (size_t)n * g * field * 4)) != DRF_OK) return rc;
         if ((rc = dev_alloc(den, (void**)&den->anchor, field * 4)) != DRF_OK) return rc;
-        den->cap_sample_n = n; den->cap_sample_field = (int)field; den->cap_sample_g = g;
+        den->cap_sample_n = n; den->cap_sample_field = field; den->cap_sample_g = g;
     }
     size_t crow = 0;
     switch (den->cfg.cond) {
@@ -638,16 +739,15 @@ extern "C" drf_status drf_sample_noise(drf_denoiser* den, const drf_sched_config
     }
     if (den->cond_cat_bytes < crow * gB) {
         DRF_HIP(hipStreamSynchronize(st));
-        dev_free(den, den->cond_cat);
         den->cond_cat_bytes = 0;
+        dev_free(den, &den->cond_cat);
         if ((rc = dev_alloc(den, &den->cond_cat, crow * gB)) != DRF_OK) return rc;
         den->cond_cat_bytes = crow * gB;
     }
     DRF_HIP(hipMemcpyAsync(den->cond_cat, cond, crow * batch, hipMemcpyDeviceToDevice, st));
     if (g == 2) DRF_HIP(hipMemcpyAsync((char*)den->cond_cat + crow * batch, null_cond, crow * batch, hipMemcpyDeviceToDevice, st));
     if ((rc = ensure_workspace(den, n * gB, st)) != DRF_OK) return rc;
-    // cross-attention K/V depend only on the context: once per call, for the g*B distinct rows
-    if (den->cfg.cond == DRF_COND_TEXT && (rc = compute_ctx_kv(den, (const float*)den->cond_cat, gB, st)) != DRF_OK) return rc;
+    if ((rc = ensure_ctx(den, gB, st)) != DRF_OK) return rc;
 
     // The conditioning of every pass is known up front (timesteps from the plan, per-sample
     // cond rows): all modulation rows of the call are produced by a few large launches instead of
@@ -656,13 +756,16 @@ extern "C" drf_status drf_sample_noise(drf_denoiser* den, const drf_sched_config
     for (const Pass& p : passes) total_groups += p.eval_s.size();
     if (total_groups * gB > (size_t)1 << 24) DRF_FAIL(DRF_EINVAL, "steps * batch too large");
     if ((rc = ensure_cond(den, (int)(total_groups * gB), st)) != DRF_OK) return rc;
+    const Workspace& ws = den->ws;
+    // cross-attention K/V depend only on the context: once per call, for the g*B distinct rows
+    if (den->cfg.cond == DRF_COND_TEXT && (rc = compute_ctx_kv(den, ws, (const float*)den->cond_cat, gB, st)) != DRF_OK) return rc;
     {
         SlotMap map{};
         map.t_dev = nullptr; map.group = gB; map.x_group = 1; map.x_batch = 1; map.cond_mod = gB;
         int ng = 0, row0 = 0;
         auto flush = [&]() -> drf_status {
             if (ng == 0) return DRF_OK;
-            drf_status r = conditioning(den, map, den->cond_cat, ng * gB, row0, den->mod + (size_t)row0 * den->n_mod, st);
+            drf_status r = conditioning(den, ws, map, den->cond_cat, ng * gB, row0, ws.mod + (size_t)row0 * den->n_mod, st);
             row0 += ng * gB; ng = 0;
             return r;
         };
@@ -683,7 +786,11 @@ extern "C" drf_status drf_sample_noise(drf_denoiser* den, const drf_sched_config
         map.t_dev = nullptr; map.group = gB; map.x_group = gB; map.x_batch = batch; map.cond_mod = gB;
         for (int i = 0; i < groups; ++i) map.taus[i] = sch.net_time(p.eval_s[(size_t)i]);
         const float* xin = p.solo ? x_anchor : den->drafts;
-        if ((rc = forward(den, xin, map, den->mod + mod_row * den->n_mod, groups * gB, dm.L, den->epsbuf, nullptr, st)) != DRF_OK) return rc;
+        {
+            ProfScope pass_scope(den, st, !p.solo && groups == n ? DRF_PROF_PASS_FULL : DRF_PROF_PASS_OTHER,
+                                 (double)groups * gB * slot_eval_flops(den));
+            if ((rc = forward(den, ws, xin, map, ws.mod + mod_row * den->n_mod, groups * gB, dm.L, den->epsbuf, nullptr, st)) != DRF_OK) return rc;
+        }
         mod_row += (size_t)groups * gB;
 
         UpdateArgs& u = updates[k];
@@ -704,13 +811,14 @@ extern "C" drf_status drf_sample_noise(drf_denoiser* den, const drf_sched_config
         ProfScope ps(den, st, DRF_PROF_UPDATE, bytes);
         if ((rc = launch_update(u, st)) != DRF_OK) return rc;
     }
-    return DRF_OK;
+    return mark_in_flight(den, st);
 }
 
 extern "C" drf_status drf_profile_enable(drf_denoiser* den, int on)
 {
     if (!den) DRF_FAIL(DRF_EINVAL, "denoiser is NULL");
-    den->prof.on = on != 0;
+    if (on < 0 || on > 2) DRF_FAIL(DRF_EINVAL, "profile mode %d outside 0..2", on);
+    den->prof.on = on;
     return DRF_OK;
 }
 
@@ -732,18 +840,13 @@ extern "C" drf_status drf_profile_read(drf_denoiser* den, int which, long long* 
     return DRF_OK;
 }
 
-namespace drf { extern int g_gemm_variant; }
-
 extern "C" drf_status drf_probe_gemm_bf16(const void* A, const void* W, int M, int N, int K, void* out_bf16,
                                           const float* bias, int variant, void* hip_stream)
 {
     if (!A || !W || !out_bf16 || !bias || M < 0 || N < 0 || K < 0) DRF_FAIL(DRF_EINVAL, "bad argument");
     Epilogue e{};
     e.mode = EPI_STORE; e.out = out_bf16; e.ldo = N; e.out_f32 = 0; e.bias = bias;
-    drf::g_gemm_variant = variant;
-    drf_status rc = launch_gemm_bf16((const bf16_t*)A, (const bf16_t*)W, M, N, K, e, (hipStream_t)hip_stream);
-    drf::g_gemm_variant = 0;
-    return rc;
+    return launch_gemm_bf16((const bf16_t*)A, (const bf16_t*)W, M, N, K, e, (hipStream_t)hip_stream, variant);
 }
 
 extern "C" drf_status drf_probe_attn_bf16(const void* qkv, void* out, int slots, int tokens, int heads, int head_dim,

@@ -1,6 +1,7 @@
 // GEMM C[M][N] = A[M][K] . W[N][K]^T with fused epilogues (bias, GELU-tanh, gated
-// residual).  bf16 path: MFMA 32x32x16 tiles fed from LDS, fp32 accumulate.
-// fp32 path: plain LDS-tiled FMA kernel for the fp32 configuration.
+// residual).  bf16 path: the wide-tile kernel (16x16x32 MFMAs, operands by LDS-DMA) for the
+// DiT's big GEMMs and a small 32x32x16-MFMA kernel for short or ragged problems, fp32
+// accumulate.  fp32 path: plain LDS-tiled FMA kernel for the fp32 configuration.
 #include <type_traits>
 
 #include "common.h"
@@ -602,9 +603,8 @@ drf_status launch_bf16_xl(const bf16_t* A, const bf16_t* W, int M, int N, int K,
 
 }  // namespace
 
-int g_gemm_variant = 0;   // measurement hook: 0 = heuristic, else force a tile shape
-
-drf_status launch_gemm_bf16(const bf16_t* A, const bf16_t* W, int M, int N, int K, const Epilogue& e, hipStream_t st)
+drf_status launch_gemm_bf16(const bf16_t* A, const bf16_t* W, int M, int N, int K, const Epilogue& e, hipStream_t st,
+                            int variant)
 {
     if (M == 0 || N == 0) return DRF_OK;
     if (K % 64 != 0 || N % 4 != 0 || e.ldo % 4 != 0) DRF_FAIL(DRF_ESHAPE, "bf16 GEMM needs K %% 64 == 0 and N %% 4 == 0 (M=%d N=%d K=%d)", M, N, K);
@@ -613,7 +613,7 @@ drf_status launch_gemm_bf16(const bf16_t* A, const bf16_t* W, int M, int N, int 
     if (e.mode == EPI_STORE_GATED && (e.out_f32 || !e.gate)) DRF_FAIL(DRF_ESHAPE, "gated store needs bf16 output and a gate");
     if ((size_t)M * K >= ((size_t)1 << 31) || (size_t)N * K >= ((size_t)1 << 31))
         DRF_FAIL(DRF_ESHAPE, "bf16 GEMM operand exceeds 2^31 elements");
-    int v = g_gemm_variant;
+    int v = variant;
     if (v == 0) {
         // Pick the tile shape that wastes the least MFMA work: padding of the last tile row /
         // column, and the idle CUs of the last round of 256 concurrent tiles.

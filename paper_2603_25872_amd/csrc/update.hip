@@ -3,6 +3,7 @@
 // one pass over the latent fields (Algorithm 1 / Algorithm 2, everything except the
 // predictor).  HBM-bound: every input element is read once, every output written once.
 #include "common.h"
+#include "../../include/drf_measure.h"
 
 namespace drf {
 
@@ -238,4 +239,31 @@ extern "C" drf_status drf_refine_step(const drf_sched_config* sched, const float
     if (s_from < 1) DRF_FAIL(DRF_EINVAL, "s_from must be >= 1 (got %d)", s_from);
     const int to = s_from - 1;
     return drf_skip_transition(sched, x, eps, s_from, &to, 1, batch, elems_per_sample, x_out, hip_stream);
+}
+
+extern "C" drf_status drf_probe_update_fused(const drf_sched_config* sched, int s_from, int n_chain, int n_draft, int g,
+                                             float w, size_t field, const float* x_base, const float* eps, float* x_out,
+                                             float* draft_out, void* hip_stream)
+{
+    Schedule sch;
+    drf_status rc = make_schedule(sched, &sch);
+    if (rc != DRF_OK) return rc;
+    if (sch.stochastic()) DRF_FAIL(DRF_EINVAL, "the probe takes samplers without variance");
+    if (n_chain < 0 || n_draft < 0 || n_chain > kMaxBlock || n_draft > kMaxBlock || (g != 1 && g != 2))
+        DRF_FAIL(DRF_EINVAL, "bad chain / draft / guidance counts");
+    if (s_from < 0 || s_from > sch.steps || s_from - n_chain - n_draft < 0) DRF_FAIL(DRF_EINVAL, "chain and drafts run past index 0");
+    if (field == 0) return DRF_OK;
+    if (!x_base || !eps || (n_draft > 0 && !draft_out) || (!x_out && n_draft == 0)) DRF_FAIL(DRF_EINVAL, "NULL buffer");
+    UpdateArgs a{};
+    a.x_base = x_base; a.eps = eps; a.x_out = x_out; a.draft_out = n_draft > 0 ? draft_out : nullptr;
+    a.field = field; a.g = g; a.w = w; a.n_chain = n_chain; a.n_draft = n_draft;
+    a.anchor_field = n_chain > 0 ? n_chain - 1 : 0;
+    float c_unused = 0.f;
+    for (int i = 0; i < n_chain; ++i)
+        if ((rc = sch.coef(s_from - i, s_from - i - 1, &a.cA[i], &a.cB[i], &c_unused)) != DRF_OK) return rc;
+    const int s_mid = s_from - n_chain;
+    for (int j = 0; j < n_draft; ++j)
+        if ((rc = sch.coef(s_mid, s_mid - j - 1, &a.dA[j], &a.dB[j], &c_unused)) != DRF_OK) return rc;
+    if ((rc = set_noise_source(&a, nullptr)) != DRF_OK) return rc;
+    return launch_update(a, (hipStream_t)hip_stream);
 }

@@ -15,13 +15,17 @@ CONSERVATIVE, AGGRESSIVE = 0, 1
 F32, BF16 = 0, 1
 COND_VECTOR, COND_CLASS, COND_TEXT = 0, 1, 2
 PLAN_ROW = 5
-PROF_GEMM, PROF_ATTN, PROF_ELEMWISE, PROF_UPDATE = 0, 1, 2, 3
+PROF_GEMM, PROF_ATTN, PROF_ELEMWISE, PROF_UPDATE, PROF_PASS_FULL, PROF_PASS_OTHER = 0, 1, 2, 3, 4, 5
 DDIM, DDPM, EULER = 0, 1, 2
 
+# include/drf.h: the method's calls
 SYMBOLS = ["drf_denoiser_weight_count", "drf_denoiser_create", "drf_denoiser_destroy", "drf_denoiser_reserve",
-           "drf_eps_batched", "drf_eps_trace", "drf_skip_transition", "drf_refine_step", "drf_sample",
+           "drf_eps_batched", "drf_skip_transition", "drf_refine_step", "drf_sample",
            "drf_skip_transition_noise", "drf_normal_fill", "drf_sample_noise", "drf_noise_count",
-           "drf_plan_build", "drf_profile_enable", "drf_profile_read", "drf_probe_gemm_bf16", "drf_probe_attn_bf16", "drf_last_error"]
+           "drf_plan_build", "drf_last_error"]
+# include/drf_measure.h: test and measurement hooks
+MEASURE_SYMBOLS = ["drf_eps_trace", "drf_profile_enable", "drf_profile_read", "drf_probe_gemm_bf16",
+                   "drf_probe_attn_bf16", "drf_probe_update_fused", "drf_calibrate_mfma_bf16", "drf_calibrate_copy"]
 
 
 class DitConfig(C.Structure):
@@ -61,6 +65,10 @@ def lib():
         L.drf_denoiser_destroy.restype = None
         L.drf_denoiser_reserve.argtypes = [C.c_void_p, C.c_int]
         L.drf_eps_batched.argtypes = [C.c_void_p, C.c_void_p, C.c_void_p, C.c_void_p, C.c_int, C.c_void_p, C.c_void_p]
+        L.drf_probe_update_fused.argtypes = [C.c_void_p, C.c_int, C.c_int, C.c_int, C.c_int, C.c_float, C.c_size_t, C.c_void_p,
+                                             C.c_void_p, C.c_void_p, C.c_void_p, C.c_void_p]
+        L.drf_calibrate_mfma_bf16.argtypes = [C.c_int, C.c_int, C.c_void_p, C.c_void_p]
+        L.drf_calibrate_copy.argtypes = [C.c_void_p, C.c_void_p, C.c_size_t, C.c_int, C.c_void_p, C.c_void_p]
         L.drf_eps_trace.argtypes = [C.c_void_p, C.c_void_p, C.c_void_p, C.c_void_p, C.c_int, C.c_int, C.c_void_p,
                                     C.c_void_p]
         L.drf_skip_transition.argtypes = [C.c_void_p, C.c_void_p, C.c_void_p, C.c_int, C.c_void_p, C.c_int, C.c_int,
@@ -225,6 +233,38 @@ def probe_attn_bf16(qkv, slots, tokens, heads, head_dim, out=None):
     return out
 
 
+def probe_update_fused(sched, s_from, n_chain, n_draft, g, w, x_base, eps, x_out=None, draft_out=None):
+    """One launch of the fused guidance + refine-chain + draft update kernel (measurement hook).
+    x_base [field...], eps [max(n_chain,1), g, field...]; returns (x_out, draft_out [n_draft, field...])."""
+    import torch
+    sc = sched_config(sched)
+    field = x_base.numel()
+    if x_out is None:
+        x_out = torch.empty_like(x_base)
+    if draft_out is None and n_draft > 0:
+        draft_out = torch.empty((n_draft,) + tuple(x_base.shape), dtype=torch.float32, device=x_base.device)
+    _check(lib().drf_probe_update_fused(C.byref(sc), s_from, n_chain, n_draft, g, float(w), field, _dev(x_base, torch.float32),
+                                        _dev(eps, torch.float32), _dev(x_out, torch.float32), _dev(draft_out, torch.float32),
+                                        _stream()))
+    return x_out, draft_out
+
+
+def calibrate_mfma_bf16(random_operands=True, iters=5):
+    """TFLOP/s of a loop of nothing but the GEMM kernel's MFMA instruction on this GPU (measurement hook)."""
+    v = C.c_double(0)
+    _check(lib().drf_calibrate_mfma_bf16(1 if random_operands else 0, iters, C.byref(v), _stream()))
+    return v.value
+
+
+def calibrate_copy(src, dst, iters=5):
+    """GB/s (read + written) of a plain copy kernel between two device tensors of equal size (measurement hook)."""
+    v = C.c_double(0)
+    nbytes = src.numel() * src.element_size()
+    assert dst.numel() * dst.element_size() == nbytes
+    _check(lib().drf_calibrate_copy(_dev(src), _dev(dst), nbytes, iters, C.byref(v), _stream()))
+    return v.value
+
+
 class Denoiser:
     """Owns a drf_denoiser handle."""
 
@@ -290,8 +330,9 @@ class Denoiser:
                                       _dev(out, torch.float32), _stream()))
         return out
 
-    def profile_enable(self, on=True):
-        _check(lib().drf_profile_enable(self.h, 1 if on else 0))
+    def profile_enable(self, on=1):
+        """0 off, 1 (True) per launch, 2 per predictor pass of sample()"""
+        _check(lib().drf_profile_enable(self.h, int(on)))
 
     def profile_read(self, which):
         n, ms, work = C.c_longlong(0), C.c_double(0), C.c_double(0)

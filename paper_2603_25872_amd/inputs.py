@@ -139,3 +139,31 @@ def conditioning(dit, batch, cfg_idx=0, null=False):
             return np.full((batch,), dit["cond_dim"], np.int32)
         return rng.integers(0, dit["cond_dim"], size=(batch,), dtype=np.int32)
     return rng.standard_normal((batch, dit["ctx_len"], dit["cond_dim"]), dtype=np.float32)
+
+
+def draft_pass(cfg_idx, taus):
+    """Inputs of ONE full draft pass of configuration `cfg_idx` in the slot order the sampler uses,
+    [draft i][cond | null][b]: seeded states x ~ N(0, 1) per slot (stream 400), the timestep taus[i]
+    repeated over the g * batch slots of draft i, and the per-sample conditioning (null rows for the
+    second half of every draft group when the configuration uses guidance).
+    `taus` come from the caller's plan (one per draft); nothing is computed here.
+    Returns (x [slots, C, H, W] fp32, t [slots] int32, cond [slots, ...])."""
+    c = CONFIGS[cfg_idx]
+    dit, B = c["dit"], c["batch"]
+    g = 2 if c["guidance"] else 1
+    m = len(taus)
+    slots = m * g * B
+    x = _rng(400, cfg_idx).standard_normal((slots, dit["in_ch"], dit["lat_h"], dit["lat_w"]), dtype=np.float32)
+    t = np.repeat(np.asarray(taus, np.int32), g * B)
+    rows = [conditioning(dit, B, cfg_idx)]
+    if g == 2:
+        rows.append(conditioning(dit, B, cfg_idx, null=True))
+    cond = np.concatenate(rows * m, axis=0)
+    return x, t, np.ascontiguousarray(cond)
+
+
+def sample_points(count, size, tag):
+    """`count` distinct flat indices into an array of `size` elements, seeded by `tag`: the
+    positions at which stored reference values of large fields are kept."""
+    rng = np.random.Generator(np.random.Philox(key=BASE_SEED + 900 + tag))
+    return np.sort(rng.choice(size, size=min(count, size), replace=False))

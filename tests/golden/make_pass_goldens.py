@@ -1,0 +1,89 @@
+"""Writes tests/golden/cfg{3,4,5}_pass.txt: reference values of ONE full draft pass of workload
+configurations 3, 4 and 5 at their stated shapes (the batched noise-predictor evaluation of the
+drafts of the first block, Algorithm 1 / Algorithm 2, every draft group with its own timestep),
+computed by the CPU oracle alone (fp64) for a few sampled slots.  Nothing from the HIP library is
+imported or called.
+
+Per sampled slot the file holds, at seeded sample positions (inputs.sample_points):
+  loud init  : the residual stream after block 1 and after the last block, and eps
+               (configuration 4: no eps, the two full-depth runs it has are ~10 minutes each)
+  paper init : eps
+The "loud" initialisation (test-only) makes the attention and MLP branches carry O(1) signal.
+
+    python tests/golden/make_pass_goldens.py [3] [4] [5]
+
+Run time on 8 cores: configuration 3 ~2 min, 5 ~10 min, 4 ~40 min.
+"""
+import os
+import sys
+import time
+
+import numpy as np
+
+ROOT = os.path.dirname(os.path.dirname(os.path.dirname(os.path.abspath(__file__))))
+sys.path.insert(0, ROOT)
+
+from oracle.ref import Oracle                      # noqa: E402
+from paper_2603_25872_amd import inputs as I       # noqa: E402  (seeded input generators only)
+
+# sampled slots: different draft groups (timesteps), cond and null halves
+SLOTS = {3: (5, 62), 4: (2, 5), 5: (3, 37, 63)}
+N_RESID, N_EPS = 1024, 2048
+
+
+def first_draft_taus(orc, cfg):
+    """Timesteps of the first full draft round, read off the oracle's plan."""
+    rows = orc.plan(cfg["sched"], cfg["mode"], cfg["n"])
+    first = min(r[0] for r in rows.tolist() if r[1] == 1)
+    return [r[4] for r in rows.tolist() if r[0] == first and r[1] == 1 and r[4] >= 0]
+
+
+def records(idx):
+    """(record name, init, slot, what) in file order."""
+    out = []
+    for s in SLOTS[idx]:
+        out.append(("loud.resid1.slot%d" % s, "loud", s, 1))
+        out.append(("loud.residL.slot%d" % s, "loud", s, "L"))
+        if idx != 4:
+            out.append(("loud.eps.slot%d" % s, "loud", s, "eps"))
+        out.append(("paper.eps.slot%d" % s, "paper", s, "eps"))
+    return out
+
+
+def main(which):
+    orc = Oracle(64)
+    for idx in which:
+        cfg = I.config(idx)
+        dit = cfg["dit"]
+        taus = first_draft_taus(orc, cfg)
+        x, t, cond = I.draft_pass(idx, taus)
+        T = (dit["lat_h"] // dit["patch"]) * (dit["lat_w"] // dit["patch"])
+        rsz, esz = T * dit["hidden"], dit["in_ch"] * dit["lat_h"] * dit["lat_w"]
+        W = {}
+        lines, t0 = [], time.perf_counter()
+        for name, init, s, what in records(idx):
+            if init not in W:
+                W.clear()
+                W[init] = orc.prepare_weights(I.weights(dit, idx, init))
+            xs, ts, cs = x[s:s + 1], t[s:s + 1], cond[s:s + 1]
+            if what == "eps":
+                v = orc.dit_eps(dit, W[init], xs, ts, cs).ravel()
+                pts = I.sample_points(N_EPS, esz, idx * 100 + s)
+            else:
+                k = dit["depth"] if what == "L" else what
+                v = orc.dit_eps(dit, W[init], xs, ts, cs, stop_blocks=k).ravel()
+                pts = I.sample_points(N_RESID, rsz, idx * 100 + s)
+            lines.append("# %s  count %d  max|v| %.10e  rms %.10e" % (name, pts.size, np.abs(v).max(), np.sqrt((v * v).mean())))
+            lines += ["%.10e" % float(q) for q in v[pts]]
+            print("cfg %d %s done at %.0f s" % (idx, name, time.perf_counter() - t0), flush=True)
+        out = os.path.join(os.path.dirname(os.path.abspath(__file__)), "cfg%d_pass.txt" % idx)
+        with open(out, "w") as f:
+            f.write("# one draft pass of configuration %d, taus %s, CPU oracle fp64, %d threads, %.0f s\n"
+                    % (idx, taus, orc.threads(), time.perf_counter() - t0))
+            f.write("# records: name, sample count, max-norm and rms of the WHOLE field; then the values at inputs.sample_points\n")
+            f.write("\n".join(lines) + "\n")
+        print("wrote", out, flush=True)
+
+
+if __name__ == "__main__":
+    main([int(a) for a in sys.argv[1:]] or [3, 5, 4])

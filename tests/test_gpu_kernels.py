@@ -101,3 +101,30 @@ def test_config3_pass_at_benchmark_size_sampled_slots(torch, drf, orc):
         want = orc.dit_eps(dit, wd, x[j:j + 1], t[j:j + 1], cls[j:j + 1])[0]
         err = np.abs(got[j] - want).max() / np.abs(want).max()
         assert err < 2e-2, (j, err)
+
+
+@pytest.mark.parametrize("g,n_chain,n_draft", [(2, 4, 4), (1, 3, 0), (2, 0, 4), (1, 1, 1)])
+def test_fused_update_probe_equals_its_parts(torch, drf, orc, g, n_chain, n_draft):
+    """The measurement hook that launches the fused guidance + chain + draft update once, against the same steps
+    made of refine_step / skip_transition calls and against the oracle's operator."""
+    sd = dict(train_steps=1000, beta_start=1e-4, beta_end=0.02, steps=50, eta=0.0)
+    rng = np.random.default_rng(g * 100 + n_chain * 10 + n_draft)
+    shape, s_from, w = (3, 4, 8, 8), 20, 4.0
+    x = rng.standard_normal(shape).astype(np.float32)
+    eps = rng.standard_normal((max(n_chain, 1), g) + shape).astype(np.float32)
+    xd, ed = torch.from_numpy(x).cuda(), torch.from_numpy(eps).cuda()
+    x_out, drafts = drf.probe_update_fused(sd, s_from, n_chain, n_draft, g, w, xd, ed)
+    guided = ed[:, 0] if g == 1 else ed[:, 1] + w * (ed[:, 0] - ed[:, 1])
+    y, s = xd, s_from
+    want = x.astype(np.float64)
+    gn = guided.cpu().numpy().astype(np.float64)
+    for i in range(n_chain):
+        y = drf.refine_step(sd, y, guided[i].contiguous(), s)
+        want = orc.skip(want, gn[i], orc.abar_at(sd, s), orc.abar_at(sd, s - 1))
+        s -= 1
+    assert np.abs(x_out.cpu().numpy() - y.cpu().numpy()).max() < 1e-5
+    assert np.abs(x_out.cpu().numpy() - want).max() / np.abs(want).max() < 1e-5
+    if n_draft:
+        anchor = guided[n_chain - 1 if n_chain else 0].contiguous()
+        parts = drf.skip_transition(sd, y, anchor, s, [s - j - 1 for j in range(n_draft)])
+        assert np.abs(drafts.cpu().numpy() - parts.cpu().numpy()).max() < 1e-5

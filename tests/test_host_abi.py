@@ -13,18 +13,21 @@ from paper_2603_25872_amd import drf, inputs as I
 ROOT = os.path.dirname(os.path.dirname(os.path.abspath(__file__)))
 
 
-def header_symbols():
-    text = open(os.path.join(ROOT, "include", "drf.h")).read()
+def header_symbols(name):
+    text = open(os.path.join(ROOT, "include", name)).read()
     text = re.sub(r"/\*.*?\*/", "", text, flags=re.S)
     return sorted(set(re.findall(r"\b(drf_[a-z_0-9]+)\s*\(", text)))
 
 
 def test_library_exports_every_declared_symbol():
     L = drf.lib()
-    names = header_symbols()
-    assert sorted(names) == sorted(drf.SYMBOLS)
-    for n in names:
+    assert sorted(os.listdir(os.path.join(ROOT, "include"))) == ["drf.h", "drf_measure.h"]
+    assert header_symbols("drf.h") == sorted(drf.SYMBOLS)
+    assert header_symbols("drf_measure.h") == sorted(drf.MEASURE_SYMBOLS)
+    for n in drf.SYMBOLS + drf.MEASURE_SYMBOLS:
         assert getattr(L, n) is not None
+    # the measurement hooks stay out of the method's header
+    assert not set(drf.MEASURE_SYMBOLS) & set(header_symbols("drf.h"))
 
 
 def sched(S):
