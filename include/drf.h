@@ -174,6 +174,23 @@ drf_status drf_eps_batched(drf_denoiser* den, const float* x, const int32_t* t, 
                            int slots, float* eps_out, void* hip_stream);
 
 /*
+ * drf_eps_batched for callers that cannot allocate device memory: code under HIP graph
+ * capture, tight serving loops, harnesses that forbid hipMalloc.  Same arguments, same
+ * kernels and the same results as drf_eps_batched, but the pass's scratch buffers
+ * (activations, conditioning rows, modulation table, K/V of a text context) are carved out
+ * of a static device array of DRF_STATIC_SCRATCH_BYTES that the library holds on every GPU
+ * it runs on until the process ends, instead of the handle's workspace; the call makes no
+ * device allocation and frees nothing.  A pass that needs more scratch than the array holds
+ * returns DRF_ESHAPE before any work is enqueued; DRF_EUNSUPPORTED while per-launch profiling
+ * is enabled on the handle.
+ * The array is shared by every handle and call on that GPU and keeps the last call's
+ * contents (nothing in it has to start at zero): calls that overlap on one GPU race.
+ */
+#define DRF_STATIC_SCRATCH_BYTES (32u << 20)
+drf_status drf_eps_batched_static(drf_denoiser* den, const float* x, const int32_t* t, const void* cond,
+                                  int slots, float* eps_out, void* hip_stream);
+
+/*
  * Skip transitions without a noise term.  DRF_DDIM with eta = 0 (Eq. ddim_skip_reverse,
  * zero variance; the draft line of Algorithm 1): for j < m,
  *   x_to[j] = sqrt(ab_to/ab_from) x_from + (sqrt(1-ab_to) - sqrt(ab_to/ab_from) sqrt(1-ab_from)) eps_from

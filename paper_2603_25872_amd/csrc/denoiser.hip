@@ -23,7 +23,7 @@ struct BlockW { LinearW qkv, proj, xq, xkv, xo, fc1, fc2; };
 
 // Device buffers of one batched pass beyond the caller's inputs and outputs: activations, the
 // conditioning front-end's rows and the modulation table, the K/V of a text context.  Either owned by
-// the handle (grown on demand) or handed in by the caller of forward().
+// the handle (grown on demand) or carved out of the library's static scratch array.
 struct Workspace {
     float *resid = nullptr, *mod = nullptr, *cact32 = nullptr, *cscratch = nullptr;
     void *hbuf = nullptr, *qkv = nullptr, *mid = nullptr, *ybuf = nullptr, *ybuf2 = nullptr, *cact = nullptr;
@@ -161,7 +161,7 @@ struct ProfScope {
 };
 
 // Sizes (bytes) of the Workspace members for a pass of `slots` slots, `cond_rows` conditioning rows and
-// `ctx_rows` distinct text contexts: the one table every workspace layout is built from.
+// `ctx_rows` distinct text contexts: one table both the owned and the static workspace are built from.
 struct WorkspaceBytes { size_t resid, hbuf, qkv, mid, ybuf, ybuf2, mod, cact32, cscratch, cact, xkv, ctx_act; };
 WorkspaceBytes workspace_bytes(const drf_denoiser* d, size_t slots, size_t cond_rows, size_t ctx_rows)
 {
@@ -442,9 +442,57 @@ SlotMap identity_map(const int32_t* t)
     return m;
 }
 
+// ---- the library's static scratch array ------------------------------------------------------
+// drf_eps_batched_static runs the same kernels as drf_eps_batched on buffers carved out of this array
+// instead of the handle's workspace, so that the call itself allocates nothing.  Every GPU holds its
+// own copy at its own address; in host code the array's name is only a stand-in for the symbol, so the
+// device address is looked up once per device (scratch_base) and only that pointer is ever handed to
+// kernels.  Nothing in it has to start at zero: every buffer is written by the pass before it is read.
+static __device__ __align__(256) unsigned char scratch[DRF_STATIC_SCRATCH_BYTES];
+constexpr int kMaxDevices = 64;
+std::mutex g_scratch_mu;
+unsigned char* g_scratch_base[kMaxDevices] = {};
+
+// Device address of the current device's copy of `scratch`.
+drf_status scratch_base(unsigned char** out)
+{
+    int dev = 0;
+    DRF_HIP(hipGetDevice(&dev));
+    if (dev < 0 || dev >= kMaxDevices) DRF_FAIL(DRF_EUNSUPPORTED, "device index %d beyond the %d the library tracks", dev, kMaxDevices);
+    std::lock_guard<std::mutex> lk(g_scratch_mu);
+    if (!g_scratch_base[dev]) {
+        void* p = nullptr;
+        DRF_HIP(hipGetSymbolAddress(&p, HIP_SYMBOL(scratch)));
+        if (!p) DRF_FAIL(DRF_EHIP, "static scratch array has no device address");
+        g_scratch_base[dev] = (unsigned char*)p;
+    }
+    *out = g_scratch_base[dev];
+    return DRF_OK;
+}
+
+// Lays the Workspace of a `slots`-slot pass out in the static scratch array (256-byte aligned pieces).
+drf_status carve_static(const drf_denoiser* d, int slots, Workspace* ws)
+{
+    unsigned char* base = nullptr;
+    drf_status rc = scratch_base(&base);
+    if (rc != DRF_OK) return rc;
+    const WorkspaceBytes b = workspace_bytes(d, (size_t)slots, (size_t)slots, (size_t)slots);
+    size_t off = 0;
+    auto take = [&](size_t bytes) { unsigned char* p = base + off; off += (bytes + 255) / 256 * 256; return p; };
+    ws->resid = (float*)take(b.resid); ws->hbuf = take(b.hbuf); ws->qkv = take(b.qkv); ws->mid = take(b.mid);
+    ws->ybuf = take(b.ybuf); ws->ybuf2 = take(b.ybuf2);
+    ws->mod = (float*)take(b.mod); ws->cact32 = (float*)take(b.cact32); ws->cscratch = (float*)take(b.cscratch); ws->cact = take(b.cact);
+    ws->xkv = take(b.xkv); ws->ctx_act = take(b.ctx_act);
+    if (off > (size_t)DRF_STATIC_SCRATCH_BYTES)
+        DRF_FAIL(DRF_ESHAPE, "a pass of %d slots needs %zu bytes of scratch; the static array holds %zu", slots, off,
+                 (size_t)DRF_STATIC_SCRATCH_BYTES);
+    return DRF_OK;
+}
+
 // ---- one handle in flight -----------------------------------------------------------------------
-// Work of two handles overlapping on one GPU from different streams is not supported: the kernels
-// are sized for sole occupancy of the chip.  Every enqueueing call first checks that the handle that enqueued last has finished, or
+// Work of two handles (or of the static scratch array's users) overlapping on one GPU from different
+// streams is not supported: the kernels are sized for sole occupancy of the chip and the static array
+// is shared.  Every enqueueing call first checks that the handle that enqueued last has finished, or
 // was used on the same stream (stream order then serialises the two), and records an event behind
 // its own work.  Skipped while the stream is being captured (an event recorded there cannot be queried).
 std::mutex g_flight_mu;
@@ -483,7 +531,7 @@ drf_status mark_in_flight(drf_denoiser* d, hipStream_t st)
 }
 
 drf_status eps_common(drf_denoiser* den, const float* x, const int32_t* t, const void* cond, int slots, int n_blocks,
-                      float* eps_out, float* resid_out, hipStream_t st)
+                      float* eps_out, float* resid_out, hipStream_t st, bool static_scratch = false)
 {
     if (!den) DRF_FAIL(DRF_EINVAL, "denoiser is NULL");
     if (slots < 0) DRF_FAIL(DRF_EINVAL, "slots must be >= 0");
@@ -492,10 +540,15 @@ drf_status eps_common(drf_denoiser* den, const float* x, const int32_t* t, const
     if ((size_t)slots * den->dm.T > (size_t)1 << 30) DRF_FAIL(DRF_EINVAL, "slots * tokens too large");
     drf_status rc;
     if ((rc = claim_device(den, st)) != DRF_OK) return rc;
-    if ((rc = ensure_workspace(den, slots, st)) != DRF_OK) return rc;
-    if ((rc = ensure_cond(den, slots, st)) != DRF_OK) return rc;
-    if ((rc = ensure_ctx(den, slots, st)) != DRF_OK) return rc;
-    const Workspace& ws = den->ws;
+    Workspace ws;
+    if (static_scratch) {
+        if ((rc = carve_static(den, slots, &ws)) != DRF_OK) return rc;
+    } else {
+        if ((rc = ensure_workspace(den, slots, st)) != DRF_OK) return rc;
+        if ((rc = ensure_cond(den, slots, st)) != DRF_OK) return rc;
+        if ((rc = ensure_ctx(den, slots, st)) != DRF_OK) return rc;
+        ws = den->ws;
+    }
     if (den->cfg.cond == DRF_COND_TEXT && (rc = compute_ctx_kv(den, ws, (const float*)cond, slots, st)) != DRF_OK) return rc;
     const SlotMap map = identity_map(t);
     if ((rc = conditioning(den, ws, map, cond, slots, 0, ws.mod, st)) != DRF_OK) return rc;
@@ -629,6 +682,11 @@ extern "C" drf_status drf_denoiser_create(const drf_dit_config* cfg, const float
         d->ada.w32 = nullptr;
     }
     if (hipEventCreateWithFlags(&d->done, hipEventDisableTiming) != hipSuccess) { set_error("create: event creation failed"); return fail(DRF_EHIP); }
+    // the set-up call of the library on this device: look up the device's copy of the static scratch array
+    {
+        unsigned char* base = nullptr;
+        if ((rc = scratch_base(&base)) != DRF_OK) return fail(rc);
+    }
     *out = d;
     return DRF_OK;
 }
@@ -662,6 +720,14 @@ extern "C" drf_status drf_eps_batched(drf_denoiser* den, const float* x, const i
 {
     if (slots > 0 && !eps_out) DRF_FAIL(DRF_EINVAL, "eps_out is NULL");
     return eps_common(den, x, t, cond, slots, den ? den->dm.L : 0, eps_out, nullptr, (hipStream_t)hip_stream);
+}
+
+extern "C" drf_status drf_eps_batched_static(drf_denoiser* den, const float* x, const int32_t* t, const void* cond,
+                                             int slots, float* eps_out, void* hip_stream)
+{
+    if (slots > 0 && !eps_out) DRF_FAIL(DRF_EINVAL, "eps_out is NULL");
+    if (den && den->prof.on) DRF_FAIL(DRF_EUNSUPPORTED, "per-launch profiling creates events; switch it off for the no-allocation call");
+    return eps_common(den, x, t, cond, slots, den ? den->dm.L : 0, eps_out, nullptr, (hipStream_t)hip_stream, true);
 }
 
 extern "C" drf_status drf_eps_trace(drf_denoiser* den, const float* x, const int32_t* t, const void* cond, int slots,

@@ -20,12 +20,13 @@ DDIM, DDPM, EULER = 0, 1, 2
 
 # include/drf.h: the method's calls
 SYMBOLS = ["drf_denoiser_weight_count", "drf_denoiser_create", "drf_denoiser_destroy", "drf_denoiser_reserve",
-           "drf_eps_batched", "drf_skip_transition", "drf_refine_step", "drf_sample",
+           "drf_eps_batched", "drf_eps_batched_static", "drf_skip_transition", "drf_refine_step", "drf_sample",
            "drf_skip_transition_noise", "drf_normal_fill", "drf_sample_noise", "drf_noise_count",
            "drf_plan_build", "drf_last_error"]
 # include/drf_measure.h: test and measurement hooks
 MEASURE_SYMBOLS = ["drf_eps_trace", "drf_profile_enable", "drf_profile_read", "drf_probe_gemm_bf16",
                    "drf_probe_attn_bf16", "drf_probe_update_fused", "drf_calibrate_mfma_bf16", "drf_calibrate_copy"]
+STATIC_SCRATCH_BYTES = 32 << 20
 
 
 class DitConfig(C.Structure):
@@ -65,6 +66,7 @@ def lib():
         L.drf_denoiser_destroy.restype = None
         L.drf_denoiser_reserve.argtypes = [C.c_void_p, C.c_int]
         L.drf_eps_batched.argtypes = [C.c_void_p, C.c_void_p, C.c_void_p, C.c_void_p, C.c_int, C.c_void_p, C.c_void_p]
+        L.drf_eps_batched_static.argtypes = [C.c_void_p, C.c_void_p, C.c_void_p, C.c_void_p, C.c_int, C.c_void_p, C.c_void_p]
         L.drf_probe_update_fused.argtypes = [C.c_void_p, C.c_int, C.c_int, C.c_int, C.c_int, C.c_float, C.c_size_t, C.c_void_p,
                                              C.c_void_p, C.c_void_p, C.c_void_p, C.c_void_p]
         L.drf_calibrate_mfma_bf16.argtypes = [C.c_int, C.c_int, C.c_void_p, C.c_void_p]
@@ -296,6 +298,13 @@ class Denoiser:
             out = torch.empty_like(x)
         _check(lib().drf_eps_batched(self.h, _dev(x, torch.float32), _dev(t, torch.int32),
                                      _dev(cond, self._cond_dtype()), x.shape[0], _dev(out, torch.float32), _stream()))
+        return out
+
+    def eps_batched_static(self, x, t, cond, out):
+        """drf_eps_batched on the library's static scratch array: the call allocates nothing, so `out` is required."""
+        import torch
+        _check(lib().drf_eps_batched_static(self.h, _dev(x, torch.float32), _dev(t, torch.int32),
+                                            _dev(cond, self._cond_dtype()), x.shape[0], _dev(out, torch.float32), _stream()))
         return out
 
     def eps_trace(self, x, t, cond, n_blocks):
