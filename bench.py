@@ -67,6 +67,9 @@ def main():
     ap.add_argument("--eta", type=float, default=0.0, help="DDIM: variance scale of the skip transitions")
     ap.add_argument("--shift", type=float, default=1.0, help="Euler: time shift of the sigma grid")
     ap.add_argument("--seed", type=int, default=1, help="seed of the library's noise stream (stochastic samplers)")
+    ap.add_argument("--graphs", type=int, default=2,
+                    help="0: drf_sample launches kernel by kernel; 2 (default): the launch sequence is captured into a HIP graph "
+                         "at the first (warm-up) call and replayed; 1: the library's default, capture at the second call")
     ap.add_argument("--no-cpu-baseline", action="store_true")
     ap.add_argument("--no-roofline", action="store_true")
     ap.add_argument("--calibrate", action="store_true", help="only measure the MFMA-loop and copy-kernel ceilings of this GPU")
@@ -137,6 +140,7 @@ def main():
     w = I.weights(dit, args.config)
     den = drf.Denoiser(dit, w)
     den.reserve(n * g * B)
+    den.use_graphs(args.graphs)
     xT = torch.from_numpy(I.latent_noise(dit, B, args.config)).cuda()
     cond = torch.from_numpy(I.conditioning(dit, B, args.config)).cuda()
     null = torch.from_numpy(I.conditioning(dit, B, args.config, null=True)).cuda() if cfg["guidance"] else None
@@ -154,9 +158,11 @@ def main():
     t0 = time.perf_counter()
     for _ in range(args.steps):
         step()
+    t_host = time.perf_counter() - t0               # the calls have returned; the GPU is still working
     torch.cuda.synchronize()
     dt = time.perf_counter() - t0
     assert bool(torch.isfinite(out).all())
+    gstats = den.graph_stats()
 
     evals = S * B * g                                   # slot evaluations per call
     ms_step = dt / args.steps * 1e3
@@ -168,9 +174,11 @@ def main():
         "n_gpus": 1, "steps": args.steps, "warmup": args.warmup,
         "ms_per_step": ms_step,
         "ms_per_sample": ms_step / B,
+        "host_ms_per_step_until_return": t_host / args.steps * 1e3,
         "higher_is_better": True, "scaling": "weak", "vs_baseline": None,
         "dtype": "bf16" if dit["dtype"] == I.BF16 else "f32",
         "data": "synthetic",
+        "graph_replay": {"mode": args.graphs, "calls_replayed": gstats["replays"], "captures_failed": gstats["failed"]},
         "config": {"workload": "config %d: %s, %d-step %s, %s n=%d, batch %d, guidance %s" % (
             args.config, cfg["name"], S,
             ["DDIM eta=%g" % args.eta if args.eta else "DDIM", "DDPM skip", "Euler shift=%g" % args.shift][args.sampler],

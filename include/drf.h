@@ -161,6 +161,20 @@ void drf_denoiser_destroy(drf_denoiser* den);
 drf_status drf_denoiser_reserve(drf_denoiser* den, int max_slots);
 
 /*
+ * How drf_sample / drf_sample_noise enqueue their launch sequence (the loop of Algorithm 1 / 2 is a fixed
+ * sequence of kernel launches once the arguments are known):
+ *   mode 1 (default): the first call with a given set of arguments (schedule, mode, n, batch, the
+ *           buffers' addresses, guidance scale, noise source) launches kernel by kernel; the second
+ *           captures the sequence into a HIP graph, and that and every later call with the same
+ *           arguments replay it with one graph launch (up to 8 argument sets are kept per handle);
+ *   mode 2: capture at the first call already;
+ *   mode 0: always kernel by kernel; drops the captured graphs.
+ * Results are the same bits in every mode.  Calls made while the caller's stream is itself being
+ * captured, or while profiling is enabled, always launch kernel by kernel.
+ */
+drf_status drf_denoiser_use_graphs(drf_denoiser* den, int mode);
+
+/*
  * eps_theta for `slots` samples in ONE pass, each with its own timestep: the batched
  * draft evaluation of Algorithm 1 / Algorithm 2 (the loop marked "concurrently").
  *   x        DEVICE fp32 [slots][in_ch][lat_h][lat_w]

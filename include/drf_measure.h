@@ -59,6 +59,13 @@ drf_status drf_probe_attn_bf16(const void* qkv, void* out, int slots, int tokens
                                void* hip_stream);
 
 /*
+ * Introspection for the graph-replay tests: how many drf_sample launch sequences the handle holds as
+ * instantiated graphs, how many captures failed (those argument sets launch kernel by kernel), and how
+ * many calls were served by a graph launch since the handle was created.
+ */
+drf_status drf_graph_stats(drf_denoiser* den, int* captured, int* failed, long long* replays);
+
+/*
  * Measurement hook: ONE launch of the fused update kernel in the shape drf_sample gives it after a
  * draft pass: guidance combine of the pass's noise fields (g = 2: eps = eps_null + w (eps_cond -
  * eps_null); g = 1: none), the chain of n_chain standard updates s_from -> s_from - 1 -> ... starting

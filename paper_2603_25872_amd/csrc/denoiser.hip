@@ -1,4 +1,5 @@
 // The denoiser handle, the batched DiT forward and the draft-and-refine loop.
+#include <algorithm>
 #include <cmath>
 #include <cstring>
 #include <mutex>
@@ -11,6 +12,9 @@ using namespace drf;
 namespace {
 
 constexpr int kTFreq = 256;
+constexpr int kMaxSlots = 65535;        // slots of one pass (some launches index slots by a grid dimension)
+constexpr int kCondChunkRows = 1024;    // modulation-table rows kept at a time when a call has more
+constexpr size_t kMaxGraphs = 8;        // captured drf_sample launch sequences kept per handle
 
 struct LinearW {
     const float* w32 = nullptr;     // fp32 path weights [N][K]
@@ -28,6 +32,15 @@ struct Workspace {
     float *resid = nullptr, *mod = nullptr, *cact32 = nullptr, *cscratch = nullptr;
     void *hbuf = nullptr, *qkv = nullptr, *mid = nullptr, *ybuf = nullptr, *ybuf2 = nullptr, *cact = nullptr;
     void *xkv = nullptr, *ctx_act = nullptr;    // cross-attention K/V cache [L][rows][ctx_len][2D] and its staging
+};
+
+// Arguments that fix the launch sequence of a drf_sample call, and the graph captured for them.
+struct SampleKey {
+    drf_sched_config sched; int mode, n, batch; const void *x_T, *cond, *null_cond, *x_0, *z; float cfg_scale;
+    int has_noise; uint64_t seed; uint32_t field0; unsigned ws_gen;
+};
+struct GraphEntry {
+    SampleKey key; hipGraphExec_t exec = nullptr; bool failed = false; unsigned long long last_use = 0;
 };
 
 struct Prof {
@@ -65,6 +78,13 @@ struct drf_denoiser {
     // the stream of this handle's last call and an event recorded behind that call's work
     hipStream_t last_stream = nullptr;
     hipEvent_t done = nullptr;
+    // captured launch sequences of drf_sample calls (see graph_for_call)
+    int graph_mode = 1;             // 0 never | 1 capture at the second call with the same arguments | 2 at the first
+    unsigned ws_gen = 0;            // bumped whenever a buffer that launches point into is re-allocated
+    hipStream_t cap_stream = nullptr;
+    std::vector<GraphEntry> graphs;
+    unsigned long long graph_clock = 0;
+    long long graph_replays = 0;
 };
 
 namespace {
@@ -186,6 +206,7 @@ drf_status ensure_workspace(drf_denoiser* d, int slots, hipStream_t st)
     DRF_HIP(hipStreamSynchronize(st));
     Workspace& w = d->ws;
     d->cap_slots = 0;
+    ++d->ws_gen;
     dev_free(d, &w.resid); dev_free(d, &w.hbuf); dev_free(d, &w.qkv); dev_free(d, &w.mid); dev_free(d, &w.ybuf); dev_free(d, &w.ybuf2);
     const WorkspaceBytes b = workspace_bytes(d, (size_t)slots, 0, 0);
     drf_status rc;
@@ -206,6 +227,7 @@ drf_status ensure_cond(drf_denoiser* d, int rows, hipStream_t st)
     DRF_HIP(hipStreamSynchronize(st));
     Workspace& w = d->ws;
     d->cap_cond_rows = 0;
+    ++d->ws_gen;
     dev_free(d, &w.mod); dev_free(d, &w.cact32); dev_free(d, &w.cscratch); dev_free(d, &w.cact);
     const WorkspaceBytes b = workspace_bytes(d, 0, (size_t)rows, 0);
     drf_status rc;
@@ -223,6 +245,7 @@ drf_status ensure_ctx(drf_denoiser* d, int rows, hipStream_t st)
     DRF_HIP(hipStreamSynchronize(st));
     Workspace& w = d->ws;
     d->cap_ctx_rows = 0;
+    ++d->ws_gen;
     dev_free(d, &w.xkv); dev_free(d, &w.ctx_act);
     const WorkspaceBytes b = workspace_bytes(d, 0, 0, (size_t)rows);
     drf_status rc;
@@ -530,6 +553,74 @@ drf_status mark_in_flight(drf_denoiser* d, hipStream_t st)
     return DRF_OK;
 }
 
+void drop_graphs(drf_denoiser* d)
+{
+    for (GraphEntry& g : d->graphs)
+        if (g.exec) (void)hipGraphExecDestroy(g.exec);
+    d->graphs.clear();
+}
+
+bool same_key(const SampleKey& a, const SampleKey& b)
+{
+    return a.sched.train_steps == b.sched.train_steps && a.sched.beta_start == b.sched.beta_start &&
+           a.sched.beta_end == b.sched.beta_end && a.sched.steps == b.sched.steps && a.sched.eta == b.sched.eta &&
+           a.sched.sampler == b.sched.sampler && a.sched.shift == b.sched.shift && a.mode == b.mode && a.n == b.n &&
+           a.batch == b.batch && a.x_T == b.x_T && a.cond == b.cond && a.null_cond == b.null_cond && a.x_0 == b.x_0 &&
+           a.z == b.z && a.cfg_scale == b.cfg_scale && a.has_noise == b.has_noise && a.seed == b.seed &&
+           a.field0 == b.field0 && a.ws_gen == b.ws_gen;
+}
+
+// The executable graph for a drf_sample call with arguments `key`, or *exec = NULL when this call is to
+// run eagerly (first sight of the key in mode 1, or a capture that failed).  The launch sequence is
+// captured on a stream of the handle's own (the caller's may be the legacy default stream, which cannot
+// be captured), in thread-local mode, and holds kernel nodes only: no memset, no memcpy.
+template <typename F> drf_status graph_for_call(drf_denoiser* d, const SampleKey& key, F&& enqueue, hipGraphExec_t* exec)
+{
+    *exec = nullptr;
+    GraphEntry* e = nullptr;
+    for (GraphEntry& g : d->graphs)
+        if (same_key(g.key, key)) { e = &g; break; }
+    if (!e) {
+        // entries for buffers that no longer exist go first, then the least recently used
+        for (size_t i = 0; i < d->graphs.size();)
+            if (d->graphs[i].key.ws_gen != d->ws_gen) {
+                if (d->graphs[i].exec) (void)hipGraphExecDestroy(d->graphs[i].exec);
+                d->graphs.erase(d->graphs.begin() + (long)i);
+            } else ++i;
+        if (d->graphs.size() >= kMaxGraphs) {
+            size_t lru = 0;
+            for (size_t i = 1; i < d->graphs.size(); ++i)
+                if (d->graphs[i].last_use < d->graphs[lru].last_use) lru = i;
+            if (d->graphs[lru].exec) (void)hipGraphExecDestroy(d->graphs[lru].exec);
+            d->graphs.erase(d->graphs.begin() + (long)lru);
+        }
+        GraphEntry ne; ne.key = key; ne.last_use = ++d->graph_clock;
+        d->graphs.push_back(ne);
+        if (d->graph_mode != 2) return DRF_OK;      // first sight: eager
+        e = &d->graphs.back();
+    }
+    e->last_use = ++d->graph_clock;
+    if (e->failed) return DRF_OK;
+    if (!e->exec) {
+        if (!d->cap_stream) DRF_HIP(hipStreamCreateWithFlags(&d->cap_stream, hipStreamNonBlocking));
+        DRF_HIP(hipStreamBeginCapture(d->cap_stream, hipStreamCaptureModeThreadLocal));
+        const drf_status rc = enqueue(d->cap_stream);
+        hipGraph_t graph = nullptr;
+        const hipError_t ee = hipStreamEndCapture(d->cap_stream, &graph);
+        hipGraphExec_t ex = nullptr;
+        if (rc == DRF_OK && ee == hipSuccess && graph && hipGraphInstantiate(&ex, graph, nullptr, nullptr, 0) == hipSuccess) {
+            e->exec = ex;
+        } else {
+            (void)hipGetLastError();
+            e->failed = true;                       // this key runs eagerly from now on
+        }
+        if (graph) (void)hipGraphDestroy(graph);
+        if (rc != DRF_OK) return rc;
+    }
+    *exec = e->exec;
+    return DRF_OK;
+}
+
 drf_status eps_common(drf_denoiser* den, const float* x, const int32_t* t, const void* cond, int slots, int n_blocks,
                       float* eps_out, float* resid_out, hipStream_t st, bool static_scratch = false)
 {
@@ -538,6 +629,7 @@ drf_status eps_common(drf_denoiser* den, const float* x, const int32_t* t, const
     if (slots == 0) return DRF_OK;
     if (!x || !t || !cond || (!eps_out && !resid_out)) DRF_FAIL(DRF_EINVAL, "NULL buffer");
     if ((size_t)slots * den->dm.T > (size_t)1 << 30) DRF_FAIL(DRF_EINVAL, "slots * tokens too large");
+    if (slots > kMaxSlots) DRF_FAIL(DRF_ESHAPE, "a pass of %d slots exceeds the %d the launches cover", slots, kMaxSlots);
     drf_status rc;
     if ((rc = claim_device(den, st)) != DRF_OK) return rc;
     Workspace ws;
@@ -701,6 +793,8 @@ extern "C" void drf_denoiser_destroy(drf_denoiser* den)
             g_last_handle = nullptr;
         }
     }
+    drop_graphs(den);
+    if (den->cap_stream) (void)hipStreamDestroy(den->cap_stream);
     for (void* p : den->allocs) (void)hipFree(p);
     if (den->done) (void)hipEventDestroy(den->done);
     for (hipEvent_t ev : den->prof.pool) (void)hipEventDestroy(ev);
@@ -785,12 +879,14 @@ extern "C" drf_status drf_sample_noise(drf_denoiser* den, const drf_sched_config
     const int g = null_cond ? 2 : 1, gB = g * batch;
     const size_t E = (size_t)dm.C * dm.H * dm.W, field = (size_t)batch * E;
     if ((size_t)n * gB * dm.T > (size_t)1 << 30) DRF_FAIL(DRF_EINVAL, "n * batch * tokens too large");
+    if ((size_t)n * gB > kMaxSlots) DRF_FAIL(DRF_ESHAPE, "a pass of %zu slots exceeds the %d the launches cover", (size_t)n * gB, kMaxSlots);
 
     // buffers: drafts [n][B][E], noises [n][g][B][E], anchor [B][E], conditioning rows [g*B]
     if ((rc = claim_device(den, st)) != DRF_OK) return rc;
     if (n > den->cap_sample_n || den->cap_sample_field < field || g > den->cap_sample_g) {
         DRF_HIP(hipStreamSynchronize(st));
         den->cap_sample_n = 0; den->cap_sample_field = 0; den->cap_sample_g = 0;
+        ++den->ws_gen;
         dev_free(den, &den->drafts); dev_free(den, &den->epsbuf); dev_free(den, &den->anchor);
         if ((rc = dev_alloc(den, (void**)&den->drafts, (size_t)n * field * 4)) != DRF_OK) return rc;
         if ((rc = dev_alloc(den, (void**)&den->epsbuf, (size_t)n * g * field * 4)) != DRF_OK) return rc;
@@ -806,78 +902,131 @@ extern "C" drf_status drf_sample_noise(drf_denoiser* den, const drf_sched_config
     if (den->cond_cat_bytes < crow * gB) {
         DRF_HIP(hipStreamSynchronize(st));
         den->cond_cat_bytes = 0;
+        ++den->ws_gen;
         dev_free(den, &den->cond_cat);
         if ((rc = dev_alloc(den, &den->cond_cat, crow * gB)) != DRF_OK) return rc;
         den->cond_cat_bytes = crow * gB;
     }
-    DRF_HIP(hipMemcpyAsync(den->cond_cat, cond, crow * batch, hipMemcpyDeviceToDevice, st));
-    if (g == 2) DRF_HIP(hipMemcpyAsync((char*)den->cond_cat + crow * batch, null_cond, crow * batch, hipMemcpyDeviceToDevice, st));
     if ((rc = ensure_workspace(den, n * gB, st)) != DRF_OK) return rc;
     if ((rc = ensure_ctx(den, gB, st)) != DRF_OK) return rc;
+    // The conditioning of the passes is known up front (timesteps from the plan, per-sample cond rows): the
+    // modulation rows of many passes are produced by a few large launches instead of one small,
+    // weight-bandwidth-bound GEMM per pass.  The table holds the rows of a chunk of consecutive passes
+    // (at least one pass, otherwise up to kCondChunkRows rows), so its size does not grow with the
+    // number of sampling steps times the batch.
+    size_t max_pass_rows = 0;
+    for (const Pass& p : passes) max_pass_rows = std::max(max_pass_rows, p.eval_s.size() * (size_t)gB);
+    const size_t table_rows = std::max(max_pass_rows, (size_t)kCondChunkRows);
+    if ((rc = ensure_cond(den, (int)table_rows, st)) != DRF_OK) return rc;
 
-    // The conditioning of every pass is known up front (timesteps from the plan, per-sample
-    // cond rows): all modulation rows of the call are produced by a few large launches instead of
-    // one small, weight-bandwidth-bound GEMM per pass.  Rows are laid out pass after pass.
-    size_t total_groups = 0;
-    for (const Pass& p : passes) total_groups += p.eval_s.size();
-    if (total_groups * gB > (size_t)1 << 24) DRF_FAIL(DRF_EINVAL, "steps * batch too large");
-    if ((rc = ensure_cond(den, (int)(total_groups * gB), st)) != DRF_OK) return rc;
+    // the caller's conditioning rows, cond then null: copied eagerly (also ahead of a graph replay)
+    DRF_HIP(hipMemcpyAsync(den->cond_cat, cond, crow * batch, hipMemcpyDeviceToDevice, st));
+    if (g == 2) DRF_HIP(hipMemcpyAsync((char*)den->cond_cat + crow * batch, null_cond, crow * batch, hipMemcpyDeviceToDevice, st));
+
+    // Everything after this point is a fixed sequence of kernel launches whose arguments depend only on
+    // the call's arguments and the handle's buffers.
     const Workspace& ws = den->ws;
-    // cross-attention K/V depend only on the context: once per call, for the g*B distinct rows
-    if (den->cfg.cond == DRF_COND_TEXT && (rc = compute_ctx_kv(den, ws, (const float*)den->cond_cat, gB, st)) != DRF_OK) return rc;
-    {
-        SlotMap map{};
-        map.t_dev = nullptr; map.group = gB; map.x_group = 1; map.x_batch = 1; map.cond_mod = gB;
-        int ng = 0, row0 = 0;
-        auto flush = [&]() -> drf_status {
-            if (ng == 0) return DRF_OK;
-            drf_status r = conditioning(den, ws, map, den->cond_cat, ng * gB, row0, ws.mod + (size_t)row0 * den->n_mod, st);
-            row0 += ng * gB; ng = 0;
-            return r;
-        };
-        for (const Pass& p : passes)
-            for (int s_eval : p.eval_s) {
-                map.taus[ng++] = sch.net_time(s_eval);
-                if (ng == kMaxBlock && (rc = flush()) != DRF_OK) return rc;
+    auto enqueue = [&](hipStream_t es) -> drf_status {
+        drf_status r;
+        // cross-attention K/V depend only on the context: once per call, for the g*B distinct rows
+        if (den->cfg.cond == DRF_COND_TEXT && (r = compute_ctx_kv(den, ws, (const float*)den->cond_cat, gB, es)) != DRF_OK) return r;
+        const float* x_anchor = x_T;                // state the next stand-alone pass evaluates
+        size_t chunk_end = 0, mod_row = 0;          // passes [.., chunk_end) have their rows in the table; next free row
+        for (size_t k = 0; k < passes.size(); ++k) {
+            const Pass& p = passes[k];
+            const int groups = (int)p.eval_s.size();
+            if (k == chunk_end) {
+                // conditioning rows of the next chunk of passes, laid out pass after pass from row 0
+                SlotMap cmap{};
+                cmap.t_dev = nullptr; cmap.group = gB; cmap.x_group = 1; cmap.x_batch = 1; cmap.cond_mod = gB;
+                int ng = 0, row0 = 0;
+                size_t rows = 0;
+                auto flush = [&]() -> drf_status {
+                    if (ng == 0) return DRF_OK;
+                    drf_status fr = conditioning(den, ws, cmap, den->cond_cat, ng * gB, row0, ws.mod + (size_t)row0 * den->n_mod, es);
+                    row0 += ng * gB; ng = 0;
+                    return fr;
+                };
+                while (chunk_end < passes.size() && (rows == 0 || rows + passes[chunk_end].eval_s.size() * gB <= table_rows)) {
+                    for (int s_eval : passes[chunk_end].eval_s) {
+                        cmap.taus[ng++] = sch.net_time(s_eval);
+                        if ((ng == kMaxBlock || (size_t)(ng + 1) * gB > (size_t)kMaxSlots) && (r = flush()) != DRF_OK) return r;
+                    }
+                    rows += passes[chunk_end].eval_s.size() * gB;
+                    ++chunk_end;
+                }
+                if ((r = flush()) != DRF_OK) return r;
+                mod_row = 0;
             }
-        if ((rc = flush()) != DRF_OK) return rc;
-    }
+            SlotMap map{};
+            map.t_dev = nullptr; map.group = gB; map.x_group = gB; map.x_batch = batch; map.cond_mod = gB;
+            for (int i = 0; i < groups; ++i) map.taus[i] = sch.net_time(p.eval_s[(size_t)i]);
+            const float* xin = p.solo ? x_anchor : den->drafts;
+            {
+                ProfScope pass_scope(den, es, !p.solo && groups == n ? DRF_PROF_PASS_FULL : DRF_PROF_PASS_OTHER,
+                                     (double)groups * gB * slot_eval_flops(den));
+                if ((r = forward(den, ws, xin, map, ws.mod + mod_row * den->n_mod, groups * gB, dm.L, den->epsbuf, nullptr, es)) != DRF_OK) return r;
+            }
+            mod_row += (size_t)groups * gB;
 
-    const float* x_anchor = x_T;                    // state the next stand-alone pass evaluates
-    size_t mod_row = 0;
-    for (size_t k = 0; k < passes.size(); ++k) {
-        const Pass& p = passes[k];
-        const int groups = (int)p.eval_s.size();
-        SlotMap map{};
-        map.t_dev = nullptr; map.group = gB; map.x_group = gB; map.x_batch = batch; map.cond_mod = gB;
-        for (int i = 0; i < groups; ++i) map.taus[i] = sch.net_time(p.eval_s[(size_t)i]);
-        const float* xin = p.solo ? x_anchor : den->drafts;
-        {
-            ProfScope pass_scope(den, st, !p.solo && groups == n ? DRF_PROF_PASS_FULL : DRF_PROF_PASS_OTHER,
-                                 (double)groups * gB * slot_eval_flops(den));
-            if ((rc = forward(den, ws, xin, map, ws.mod + mod_row * den->n_mod, groups * gB, dm.L, den->epsbuf, nullptr, st)) != DRF_OK) return rc;
+            UpdateArgs& u = updates[k];
+            u.x_base = p.base_is_draft ? den->drafts : x_anchor;
+            u.eps = den->epsbuf; u.field = field; u.g = g; u.w = cfg_scale;
+            u.anchor_field = p.anchor_field < 0 ? 0 : p.anchor_field;
+            if (p.writes_x0) {
+                if (u.n_draft > 0) { u.draft_out = x_0_out; u.x_out = nullptr; }      // the lone draft to index 0 is x_0
+                else { u.x_out = x_0_out; u.draft_out = nullptr; }
+            } else if (u.n_draft > 0) {
+                // drafts overwrite the buffer the chain started from: each element is read before it is written
+                u.draft_out = den->drafts; u.x_out = nullptr;
+            } else {
+                u.x_out = den->anchor; u.draft_out = nullptr;
+                x_anchor = den->anchor;
+            }
+            const double bytes = (double)field * 4.0 * (1.0 + (double)g * (u.n_chain + (u.n_draft > 0 ? 1 : 0)) + (u.x_out ? 1 : 0) + u.n_draft);
+            ProfScope ps(den, es, DRF_PROF_UPDATE, bytes);
+            if ((r = launch_update(u, es)) != DRF_OK) return r;
         }
-        mod_row += (size_t)groups * gB;
+        return DRF_OK;
+    };
 
-        UpdateArgs& u = updates[k];
-        u.x_base = p.base_is_draft ? den->drafts : x_anchor;
-        u.eps = den->epsbuf; u.field = field; u.g = g; u.w = cfg_scale;
-        u.anchor_field = p.anchor_field < 0 ? 0 : p.anchor_field;
-        if (p.writes_x0) {
-            if (u.n_draft > 0) { u.draft_out = x_0_out; u.x_out = nullptr; }      // the lone draft to index 0 is x_0
-            else { u.x_out = x_0_out; u.draft_out = nullptr; }
-        } else if (u.n_draft > 0) {
-            // drafts overwrite the buffer the chain started from: each element is read before it is written
-            u.draft_out = den->drafts; u.x_out = nullptr;
-        } else {
-            u.x_out = den->anchor; u.draft_out = nullptr;
-            x_anchor = den->anchor;
+    // Graph replay: the launch sequence of a call is captured once into a HIP graph and replayed by later
+    // calls with the same arguments (same schedule, mode, n, batch, buffers, guidance, noise source), which
+    // removes the per-launch host cost that bounds the small configurations.  The first call with a new set
+    // of arguments runs eagerly; the second captures.  Not used while profiling or inside a caller's capture.
+    SampleKey key{};
+    key.sched = *sched; key.mode = mode; key.n = n; key.batch = batch; key.x_T = x_T; key.cond = cond; key.null_cond = null_cond;
+    key.cfg_scale = cfg_scale; key.x_0 = x_0_out; key.ws_gen = den->ws_gen;
+    if (noise) { key.has_noise = 1; key.z = noise->z; key.seed = noise->seed; key.field0 = noise->field0; }
+    if (den->graph_mode != 0 && den->prof.on == 0 && !capturing(st)) {
+        hipGraphExec_t exec = nullptr;
+        if ((rc = graph_for_call(den, key, enqueue, &exec)) != DRF_OK) return rc;
+        if (exec) {
+            DRF_HIP(hipGraphLaunch(exec, st));
+            ++den->graph_replays;
+            return mark_in_flight(den, st);
         }
-        const double bytes = (double)field * 4.0 * (1.0 + (double)g * (u.n_chain + (u.n_draft > 0 ? 1 : 0)) + (u.x_out ? 1 : 0) + u.n_draft);
-        ProfScope ps(den, st, DRF_PROF_UPDATE, bytes);
-        if ((rc = launch_update(u, st)) != DRF_OK) return rc;
     }
+    if ((rc = enqueue(st)) != DRF_OK) return rc;
     return mark_in_flight(den, st);
+}
+
+extern "C" drf_status drf_denoiser_use_graphs(drf_denoiser* den, int mode)
+{
+    if (!den) DRF_FAIL(DRF_EINVAL, "denoiser is NULL");
+    if (mode < 0 || mode > 2) DRF_FAIL(DRF_EINVAL, "graph mode %d outside 0..2", mode);
+    den->graph_mode = mode;
+    if (mode == 0) drop_graphs(den);
+    return DRF_OK;
+}
+
+extern "C" drf_status drf_graph_stats(drf_denoiser* den, int* captured, int* failed, long long* replays)
+{
+    if (!den || !captured || !failed || !replays) DRF_FAIL(DRF_EINVAL, "bad argument");
+    *captured = *failed = 0;
+    for (const GraphEntry& g : den->graphs) { *captured += g.exec ? 1 : 0; *failed += g.failed ? 1 : 0; }
+    *replays = den->graph_replays;
+    return DRF_OK;
 }
 
 extern "C" drf_status drf_profile_enable(drf_denoiser* den, int on)

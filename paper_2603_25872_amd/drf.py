@@ -19,13 +19,13 @@ PROF_GEMM, PROF_ATTN, PROF_ELEMWISE, PROF_UPDATE, PROF_PASS_FULL, PROF_PASS_OTHE
 DDIM, DDPM, EULER = 0, 1, 2
 
 # include/drf.h: the method's calls
-SYMBOLS = ["drf_denoiser_weight_count", "drf_denoiser_create", "drf_denoiser_destroy", "drf_denoiser_reserve",
+SYMBOLS = ["drf_denoiser_weight_count", "drf_denoiser_create", "drf_denoiser_destroy", "drf_denoiser_reserve", "drf_denoiser_use_graphs",
            "drf_eps_batched", "drf_eps_batched_static", "drf_skip_transition", "drf_refine_step", "drf_sample",
            "drf_skip_transition_noise", "drf_normal_fill", "drf_sample_noise", "drf_noise_count",
            "drf_plan_build", "drf_last_error"]
 # include/drf_measure.h: test and measurement hooks
 MEASURE_SYMBOLS = ["drf_eps_trace", "drf_profile_enable", "drf_profile_read", "drf_probe_gemm_bf16",
-                   "drf_probe_attn_bf16", "drf_probe_update_fused", "drf_calibrate_mfma_bf16", "drf_calibrate_copy"]
+                   "drf_probe_attn_bf16", "drf_probe_update_fused", "drf_graph_stats", "drf_calibrate_mfma_bf16", "drf_calibrate_copy"]
 STATIC_SCRATCH_BYTES = 32 << 20
 
 
@@ -65,10 +65,12 @@ def lib():
         L.drf_denoiser_destroy.argtypes = [C.c_void_p]
         L.drf_denoiser_destroy.restype = None
         L.drf_denoiser_reserve.argtypes = [C.c_void_p, C.c_int]
+        L.drf_denoiser_use_graphs.argtypes = [C.c_void_p, C.c_int]
         L.drf_eps_batched.argtypes = [C.c_void_p, C.c_void_p, C.c_void_p, C.c_void_p, C.c_int, C.c_void_p, C.c_void_p]
         L.drf_eps_batched_static.argtypes = [C.c_void_p, C.c_void_p, C.c_void_p, C.c_void_p, C.c_int, C.c_void_p, C.c_void_p]
         L.drf_probe_update_fused.argtypes = [C.c_void_p, C.c_int, C.c_int, C.c_int, C.c_int, C.c_float, C.c_size_t, C.c_void_p,
                                              C.c_void_p, C.c_void_p, C.c_void_p, C.c_void_p]
+        L.drf_graph_stats.argtypes = [C.c_void_p, C.c_void_p, C.c_void_p, C.c_void_p]
         L.drf_calibrate_mfma_bf16.argtypes = [C.c_int, C.c_int, C.c_void_p, C.c_void_p]
         L.drf_calibrate_copy.argtypes = [C.c_void_p, C.c_void_p, C.c_size_t, C.c_int, C.c_void_p, C.c_void_p]
         L.drf_eps_trace.argtypes = [C.c_void_p, C.c_void_p, C.c_void_p, C.c_void_p, C.c_int, C.c_int, C.c_void_p,
@@ -287,6 +289,16 @@ class Denoiser:
 
     def reserve(self, max_slots):
         _check(lib().drf_denoiser_reserve(self.h, max_slots))
+
+    def use_graphs(self, mode):
+        """0: sample() launches kernel by kernel; 1 (default): replays a captured graph from the second identical
+        call on; 2: captures at the first call."""
+        _check(lib().drf_denoiser_use_graphs(self.h, int(mode)))
+
+    def graph_stats(self):
+        a, b, c = C.c_int(0), C.c_int(0), C.c_longlong(0)
+        _check(lib().drf_graph_stats(self.h, C.byref(a), C.byref(b), C.byref(c)))
+        return dict(captured=a.value, failed=b.value, replays=c.value)
 
     def _cond_dtype(self):
         import torch
