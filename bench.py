@@ -72,6 +72,9 @@ def main():
                          "at the first (warm-up) call and replayed; 1: the library's default, capture at the second call")
     ap.add_argument("--no-cpu-baseline", action="store_true")
     ap.add_argument("--no-roofline", action="store_true")
+    ap.add_argument("--n-sweep", action="store_true",
+                    help="only time drf_sample at batch 1 (unless --batch is given) for n in 1, 2, 4, 8 in both modes: the one-GPU "
+                         "analogue of the paper's latency-versus-devices figure; prints one JSON line with the table")
     ap.add_argument("--calibrate", action="store_true", help="only measure the MFMA-loop and copy-kernel ceilings of this GPU")
     ap.add_argument("--update-probe", action="store_true",
                     help="only run the fused update kernel (guidance, chain of n, n next drafts) at batch 4096: the launch a "
@@ -135,6 +138,35 @@ def main():
 
     if args.update_probe:
         print(json.dumps({"update_kernel_fused_scaled": update_probe(3)}))
+        return
+
+    if args.n_sweep:
+        Bs = 1 if args.batch is None else args.batch
+        den = drf.Denoiser(dit, I.weights(dit, args.config))
+        den.use_graphs(args.graphs)
+        xs = torch.from_numpy(I.latent_noise(dit, Bs, args.config)).cuda()
+        cs = torch.from_numpy(I.conditioning(dit, Bs, args.config)).cuda()
+        ns = torch.from_numpy(I.conditioning(dit, Bs, args.config, null=True)).cuda() if cfg["guidance"] else None
+        os_ = torch.empty_like(xs)
+        table = []
+        for m_, mname in ((I.CONSERVATIVE, "conservative"), (I.AGGRESSIVE, "aggressive")):
+            for k in (1, 2, 4, 8):
+                for _ in range(max(args.warmup, 1)):
+                    den.sample(cfg["sched"], m_, k, xs, cs, ns, cfg["guidance"] or 0.0, out=os_)
+                torch.cuda.synchronize()
+                t0 = time.perf_counter()
+                for _ in range(args.steps):
+                    den.sample(cfg["sched"], m_, k, xs, cs, ns, cfg["guidance"] or 0.0, out=os_)
+                torch.cuda.synchronize()
+                ms = (time.perf_counter() - t0) / args.steps * 1e3
+                passes = int(drf.plan_build(cfg["sched"], m_, k)[:, 0].max()) + 1
+                table.append({"mode": mname, "n": k, "ms_per_call": ms, "passes": passes, "ideal_speedup": S / passes})
+        base = {r["mode"]: r["ms_per_call"] for r in table if r["n"] == 1}
+        for r in table:
+            r["speedup_vs_n1"] = base[r["mode"]] / r["ms_per_call"]
+        den.close()
+        print(json.dumps({"n_sweep": {"workload": "config %d: %s, %d-step DDIM, batch %d, guidance %s" % (
+            args.config, cfg["name"], S, Bs, cfg["guidance"]), "steps": args.steps, "rows": table}}))
         return
 
     w = I.weights(dit, args.config)
