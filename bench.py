@@ -28,7 +28,7 @@ PEAK_HBM_GBS = 8000.0
 # the same counter reads for a plain 1 GiB copy; profiles/drf_sample_cfg3_pmc_traffic_mfma.txt): per full draft pass
 # (all kernels of one 64-slot pass) and per bf16 GEMM launch on average.  Counters cannot be read inside this
 # process, so these are the committed profile's figures and only reported for the workload they were measured on.
-PASS_TRAFFIC_BYTES = {3: None}
+PASS_TRAFFIC_BYTES = {3: 4.73e10}
 GEMM_TRAFFIC_BYTES_PER_LAUNCH = {3: 1.873e8}
 
 
