@@ -533,11 +533,14 @@ drf_status claim_device(drf_denoiser* d, hipStream_t st)
     if (capturing(st)) return DRF_OK;
     std::lock_guard<std::mutex> lk(g_flight_mu);
     drf_denoiser* o = g_last_handle;
-    if (o && o != d && o->last_stream != st && o->done) {
+    if (o && o->last_stream != st && o->done) {
+        // also o == d: the same handle moved to another stream while its buffers are still in use
         const hipError_t q = hipEventQuery(o->done);
-        if (q == hipErrorNotReady)
+        if (q == hipErrorNotReady) {
+            if (o == d) DRF_FAIL(DRF_EUNSUPPORTED, "this handle still has work in flight on another stream; synchronise that stream first");
             DRF_FAIL(DRF_EUNSUPPORTED, "another denoiser handle still has work in flight on a different stream; "
                                        "synchronise that stream first (one handle in flight per process)");
+        }
         if (q != hipSuccess) (void)hipGetLastError();
     }
     return DRF_OK;

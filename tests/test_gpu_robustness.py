@@ -88,4 +88,14 @@ def test_second_handle_is_refused_while_the_first_is_in_flight(torch, drf):
         b.eps_batched(x[:2], t[:2], c[:2], out=out_b)
     torch.cuda.synchronize()
     assert torch.equal(out_b, out_a[:2])
+    # the same handle on another stream while its own work is still running: refused as well
+    a.eps_batched(x, t, c, out=out_a)
+    moved = False
+    with torch.cuda.stream(side):
+        try:
+            a.eps_batched(x[:2], t[:2], c[:2], out=out_b)
+        except drf.DrfError as e:
+            moved = e.status == -5
+    torch.cuda.synchronize()
+    assert moved
     a.close(); b.close()
