@@ -2,7 +2,7 @@
 // bf16 path: flash-style, one wave per 32 queries, scores computed transposed
 // (S^T = K Q^T) so that each lane owns one query column and the online softmax needs a
 // single cross-lane exchange; P^T feeds the second MFMA straight from registers.
-// fp32 path: one thread per query, for the fp32 configuration.
+// fp32 path: a few lanes per query over kv rows read through the cache, for the fp32 configuration.
 #include <type_traits>
 
 #include "common.h"
@@ -317,34 +317,65 @@ __global__ void __launch_bounds__(NW * 64) attn_bf16_kernel(const AttnArgs a, fl
     }
 }
 
-// fp32: one thread per query, online softmax over kv rows read through the cache.
-constexpr int kF32MaxD = 128;
-__global__ void __launch_bounds__(128) attn_f32_kernel(const AttnArgs a, float scale)
+// fp32: kLanesPerQuery lanes share a query and split the kv rows between them (lane t takes rows
+// t, t + kLanesPerQuery, ...), each with its own online-softmax state; the states are merged with
+// cross-lane exchanges at the end.  The head width is a template bound so that the per-lane query and
+// output vectors stay in registers.
+constexpr int kF32MaxD = 128, kLanesPerQuery = 8, kF32Threads = 256;
+template <int DMAX>
+__global__ void __launch_bounds__(kF32Threads) attn_f32_kernel(const AttnArgs a, float scale)
 {
-    const int slot = blockIdx.z, h = blockIdx.y, d = a.d;
-    const int q = blockIdx.x * blockDim.x + threadIdx.x;
-    if (q >= a.Nq) return;
-    const int kvb = a.kv_mod ? slot % a.kv_mod : slot;
-    const float* Q = (const float*)a.q + slot * a.q_slot_stride + h * a.q_head_stride + (size_t)q * a.ldq;
-    const float* Kp = (const float*)a.k + kvb * a.kv_batch_stride + h * a.kv_head_stride;
-    const float* Vp = (const float*)a.v + kvb * a.kv_batch_stride + h * a.kv_head_stride;
-    float qv[kF32MaxD], o[kF32MaxD];
-    for (int e = 0; e < d; ++e) { qv[e] = Q[e] * scale; o[e] = 0.f; }
-    float m_run = -INFINITY, l_run = 0.f;
-    for (int j = 0; j < a.Nk; ++j) {
-        const float* kr = Kp + (size_t)j * a.ldk;
-        float s = 0.f;
-        for (int e = 0; e < d; ++e) s = fmaf(qv[e], kr[e], s);
-        const float m_new = fmaxf(m_run, s);
-        const float alpha = expf(m_run - m_new), p = expf(s - m_new);
-        l_run = l_run * alpha + p;
-        m_run = m_new;
-        const float* vr = Vp + (size_t)j * a.ldk;
-        for (int e = 0; e < d; ++e) o[e] = fmaf(o[e], alpha, p * vr[e]);
+    const int h = blockIdx.y, d = a.d;
+    const int sub = threadIdx.x % kLanesPerQuery;
+    const int q = blockIdx.x * (kF32Threads / kLanesPerQuery) + threadIdx.x / kLanesPerQuery;
+    const bool live = q < a.Nq;
+    const int qc = live ? q : a.Nq - 1;             // lanes past the end keep their group's exchanges in step
+    for (int slot = blockIdx.z; slot < a.slots; slot += gridDim.z) {
+        const int kvb = a.kv_mod ? slot % a.kv_mod : slot;
+        const float* Q = (const float*)a.q + slot * a.q_slot_stride + h * a.q_head_stride + (size_t)qc * a.ldq;
+        const float* Kp = (const float*)a.k + kvb * a.kv_batch_stride + h * a.kv_head_stride;
+        const float* Vp = (const float*)a.v + kvb * a.kv_batch_stride + h * a.kv_head_stride;
+        float qv[DMAX], o[DMAX];
+#pragma unroll
+        for (int e = 0; e < DMAX; ++e) { qv[e] = e < d ? Q[e] * scale : 0.f; o[e] = 0.f; }
+        float m_run = -INFINITY, l_run = 0.f;
+        for (int j = sub; j < a.Nk; j += kLanesPerQuery) {
+            const float* kr = Kp + (size_t)j * a.ldk;
+            float s = 0.f;
+#pragma unroll
+            for (int e = 0; e < DMAX; ++e)
+                if (e < d) s = fmaf(qv[e], kr[e], s);
+            const float m_new = fmaxf(m_run, s);
+            const float alpha = expf(m_run - m_new), p = expf(s - m_new);
+            l_run = l_run * alpha + p;
+            m_run = m_new;
+            const float* vr = Vp + (size_t)j * a.ldk;
+#pragma unroll
+            for (int e = 0; e < DMAX; ++e)
+                if (e < d) o[e] = fmaf(o[e], alpha, p * vr[e]);
+        }
+        // merge the kLanesPerQuery partial states (a lane that saw no row has m = -inf, l = 0)
+#pragma unroll
+        for (int off = 1; off < kLanesPerQuery; off <<= 1) {
+            const float m_o = __shfl_xor(m_run, off, 64), l_o = __shfl_xor(l_run, off, 64);
+            const float m_new = fmaxf(m_run, m_o);
+            const float ca = m_run == -INFINITY ? 0.f : expf(m_run - m_new), cb = m_o == -INFINITY ? 0.f : expf(m_o - m_new);
+            l_run = l_run * ca + l_o * cb;
+#pragma unroll
+            for (int e = 0; e < DMAX; ++e) {
+                const float o_o = __shfl_xor(o[e], off, 64);
+                o[e] = o[e] * ca + o_o * cb;
+            }
+            m_run = m_new;
+        }
+        if (live) {
+            float* op = (float*)a.out + ((size_t)slot * a.Nq + q) * a.ldo + h * d;
+            const float inv = 1.f / l_run;
+#pragma unroll
+            for (int e = 0; e < DMAX; ++e)
+                if (e < d && e % kLanesPerQuery == sub) op[e] = o[e] * inv;
+        }
     }
-    float* op = (float*)a.out + ((size_t)slot * a.Nq + q) * a.ldo + h * d;
-    const float inv = 1.f / l_run;
-    for (int e = 0; e < d; ++e) op[e] = o[e] * inv;
 }
 
 template <int KS, int DT, int NW, int KC, int NB, bool PERSIST = false>
@@ -413,8 +444,13 @@ drf_status launch_attn_f32(const AttnArgs& a, hipStream_t st)
 {
     if (a.slots == 0 || a.Nq == 0) return DRF_OK;
     if (a.Nk < 1 || a.d > kF32MaxD) DRF_FAIL(DRF_ESHAPE, "fp32 attention needs head dim <= %d (got %d)", kF32MaxD, a.d);
-    const dim3 grid((a.Nq + 127) / 128, a.heads, a.slots);
-    hipLaunchKernelGGL(attn_f32_kernel, grid, dim3(128), 0, st, a, 1.f / sqrtf((float)a.d));
+    constexpr int qpb = kF32Threads / kLanesPerQuery;
+    // slots beyond the grid's z limit are covered by a stride loop inside the kernel
+    const dim3 grid((a.Nq + qpb - 1) / qpb, a.heads, a.slots < 65535 ? a.slots : 65535);
+    const float scale = 1.f / sqrtf((float)a.d);
+    if (a.d <= 32) hipLaunchKernelGGL(attn_f32_kernel<32>, grid, dim3(kF32Threads), 0, st, a, scale);
+    else if (a.d <= 64) hipLaunchKernelGGL(attn_f32_kernel<64>, grid, dim3(kF32Threads), 0, st, a, scale);
+    else hipLaunchKernelGGL(attn_f32_kernel<128>, grid, dim3(kF32Threads), 0, st, a, scale);
     DRF_HIP(hipGetLastError());
     return DRF_OK;
 }
