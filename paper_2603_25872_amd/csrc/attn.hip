@@ -412,7 +412,7 @@ drf_status launch_bf16_inst(const AttnArgs& a, float scale_log2, hipStream_t st)
             // more items than workgroups that fit the chip at once: persistent workgroups hide each next
             // item's first loads; otherwise the plain kernel (fewer registers) is the faster one
             const long long n_items = (long long)((a.Nq + 255) / 256) * a.heads * a.slots;
-            if (n_items > kPersistGroups) return launch_bf16_cfg<KS, DT, 8, 128, 2, true>(a, scale_log2, st);
+            if (n_items > kPersistGroups) return launch_bf16_cfg<KS, DT, 8, 64, 2, true>(a, scale_log2, st);
             return launch_bf16_cfg<KS, DT, 8, 64, 2>(a, scale_log2, st);
         }
         return launch_bf16_cfg<KS, DT, 8, 128, 2>(a, scale_log2, st);
