@@ -72,3 +72,35 @@ def test_static_scratch_entry_rejects_what_does_not_fit(torch, drf):
     den.eps_batched_static(x[:2], t[:2], c[:2], out[:2])
     assert torch.equal(out[:2], den.eps_batched(x[:2], t[:2], c[:2]))
     den.close()
+
+
+def test_static_scratch_entry_under_stream_capture(torch, drf):
+    """One of the callers the entry point is for: the pass is recorded into a HIP graph (torch's capture of
+    the stream the library is given) and replayed, with eager work and synchronisations between the replays;
+    every replay must give the eager bits, also after the inputs changed in place."""
+    dit = I.config(2, depth=3)["dit"]
+    den = drf.Denoiser(dit, I.weights(dit, 12, "loud"))
+    x, t, c = make(torch, dit, 6, 31)
+    out = torch.empty_like(x)
+    den.eps_batched_static(x, t, c, out)            # eager first: every kernel has been launched once
+    want = den.eps_batched(x, t, c)
+    x2 = torch.randn_like(x)
+    want2 = den.eps_batched(x2, t, c)
+    torch.cuda.synchronize()
+    graph = torch.cuda.CUDAGraph()
+    out.zero_()
+    with torch.cuda.graph(graph):
+        den.eps_batched_static(x, t, c, out)
+    torch.cuda.synchronize()
+    keep = x.clone()
+    for it in range(4):
+        if it % 2:
+            x.copy_(x2)
+        out.fill_(float("nan"))
+        graph.replay()
+        torch.cuda.synchronize()
+        assert torch.equal(out, want2 if it % 2 else want), it
+        x.copy_(keep)
+        den.eps_batched(x2[:2], t[:2], c[:2])       # eager work on the handle's own workspace between replays
+        torch.cuda.synchronize()
+    den.close()
