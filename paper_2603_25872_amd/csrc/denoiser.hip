@@ -556,10 +556,18 @@ drf_status mark_in_flight(drf_denoiser* d, hipStream_t st)
     return DRF_OK;
 }
 
+// An executable graph may still be running on the stream of the handle's last call: wait for that stream
+// before the graph's resources go (evictions and mode changes are rare; replays never come here).
+void retire_exec(drf_denoiser* d, hipGraphExec_t exec)
+{
+    if (!exec) return;
+    if (hipStreamSynchronize(d->last_stream) != hipSuccess) (void)hipGetLastError();
+    (void)hipGraphExecDestroy(exec);
+}
+
 void drop_graphs(drf_denoiser* d)
 {
-    for (GraphEntry& g : d->graphs)
-        if (g.exec) (void)hipGraphExecDestroy(g.exec);
+    for (GraphEntry& g : d->graphs) retire_exec(d, g.exec);
     d->graphs.clear();
 }
 
@@ -587,14 +595,14 @@ template <typename F> drf_status graph_for_call(drf_denoiser* d, const SampleKey
         // entries for buffers that no longer exist go first, then the least recently used
         for (size_t i = 0; i < d->graphs.size();)
             if (d->graphs[i].key.ws_gen != d->ws_gen) {
-                if (d->graphs[i].exec) (void)hipGraphExecDestroy(d->graphs[i].exec);
+                retire_exec(d, d->graphs[i].exec);
                 d->graphs.erase(d->graphs.begin() + (long)i);
             } else ++i;
         if (d->graphs.size() >= kMaxGraphs) {
             size_t lru = 0;
             for (size_t i = 1; i < d->graphs.size(); ++i)
                 if (d->graphs[i].last_use < d->graphs[lru].last_use) lru = i;
-            if (d->graphs[lru].exec) (void)hipGraphExecDestroy(d->graphs[lru].exec);
+            retire_exec(d, d->graphs[lru].exec);
             d->graphs.erase(d->graphs.begin() + (long)lru);
         }
         GraphEntry ne; ne.key = key; ne.last_use = ++d->graph_clock;
