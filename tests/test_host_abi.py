@@ -146,6 +146,21 @@ def test_null_handles_are_rejected_without_touching_the_gpu():
     assert L.drf_skip_transition(C.byref(sc), None, None, 5, to, 1, 0, 16, None, None) == 0
     assert L.drf_skip_transition(C.byref(sc), None, None, 5, to, 1, 2, 16, None, None) == -1
     assert L.drf_refine_step(C.byref(sc), None, None, 0, 1, 16, None, None) == -1
+    # the entry point that allocates nothing, the graph switch and the measurement hooks
+    assert L.drf_eps_batched_static(None, None, None, None, 1, None, None) == -1
+    assert L.drf_denoiser_use_graphs(None, 1) == -1
+    a, b, c = C.c_int(0), C.c_int(0), C.c_longlong(0)
+    assert L.drf_graph_stats(None, C.byref(a), C.byref(b), C.byref(c)) == -1
+    assert L.drf_profile_enable(None, 1) == -1
+    v = C.c_double(0)
+    assert L.drf_calibrate_mfma_bf16(1, 0, C.byref(v), None) == -1           # iters < 1
+    assert L.drf_calibrate_copy(None, None, 1024, 1, C.byref(v), None) == -1
+    # the fused-update probe validates its counts and indices on the host before any launch
+    assert L.drf_probe_update_fused(C.byref(sc), 20, 4, 4, 3, C.c_float(1), 16, None, None, None, None, None) == -1   # g not 1 | 2
+    assert L.drf_probe_update_fused(C.byref(sc), 5, 4, 4, 2, C.c_float(1), 16, None, None, None, None, None) == -1    # runs past index 0
+    assert L.drf_probe_update_fused(C.byref(sc), 20, 4, 4, 2, C.c_float(1), 0, None, None, None, None, None) == 0     # empty field: no-op
+    assert L.drf_probe_update_fused(C.byref(sc), 20, 4, 4, 2, C.c_float(1), 16, None, None, None, None, None) == -1   # NULL buffers
+    assert len(L.drf_last_error()) > 0
 
 
 def test_bench_refuses_more_than_one_gpu():
