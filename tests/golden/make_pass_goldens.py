@@ -12,7 +12,7 @@ The "loud" initialisation (test-only) makes the attention and MLP branches carry
 
     python tests/golden/make_pass_goldens.py [3] [4] [5]
 
-Run time on 8 cores: configuration 3 ~2 min, 5 ~10 min, 4 ~40 min.
+Run time on 6 of 8 cores: configuration 3 ~3 min, 5 ~13 min, 4 ~90 min (22 min per full-depth slot at 4096 tokens).
 """
 import os
 import sys
