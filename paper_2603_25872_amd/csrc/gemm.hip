@@ -215,6 +215,9 @@ template <int I, int N, typename F> __device__ __forceinline__ void static_for(F
 //    idle) LDS stages and then touches global memory in whole rows: 16 bytes per lane,
 //    consecutive lanes on consecutive addresses.
 typedef float f32x4 __attribute__((ext_vector_type(4)));
+// copy instructions issued per MFMA group by the in-loop copy of the two-stage kernels (1: measured best; 2, 3 and
+// the whole copy at once are 0.8 % slower per call, one every other group lands too late: 3 % slower)
+constexpr int kSpreadPer = 1;
 
 template <int BM, int BN, int BK, int NS, int WM, int WN, int WK = 1>
 __global__ void __launch_bounds__(WM * WN * WK * 64)
@@ -277,15 +280,22 @@ gemm_bf16_xl_kernel(const bf16_t* __restrict__ A, const bf16_t* __restrict__ W, 
         else { row = n0 + r - BM; row = row < N ? row : N - 1; }
         voff[i] = ((uint32_t)row * (uint32_t)K + (uint32_t)chunk * 8u) * 2u;
     }
+    const uint32_t lds_base = (uint32_t)(uintptr_t)(DRF_LDS_AS unsigned char*)smem_raw;
+    // instruction i (of this wave's LPT) of the copy of k-tile kt into `stage`
+    auto issue_one = [&](auto ic, int kt, int stage) {
+        constexpr int i = decltype(ic)::value;
+        int g = wave * LPT + i; g = g < SEG ? g : SEG - 1;
+        const int sub = g / SEG1, gl = g % SEG1;
+        // written by hand in the scalar-base form (uniform 64-bit base in SGPRs + the lane's 32-bit byte offset),
+        // which needs no 64-bit address registers per lane; M0 carries the wave-uniform LDS destination
+        const bf16_t* base = (gl * RPI < BM ? A : W) + (kt * WK + sub) * BK;
+        const uint32_t dst = lds_base + (uint32_t)(stage * STAGE + sub * STAGE1 + gl * RPI * BK) * 2u;
+        const uint32_t vo = voff[i];
+        asm volatile("s_mov_b32 m0, %0\n\ts_nop 0\n\tglobal_load_lds_dwordx4 %1, %2"
+                     :: "s"(dst), "v"(vo), "s"(base) : "memory");
+    };
     auto issue = [&](int kt, int stage) {
-#pragma unroll
-        for (int i = 0; i < LPT; ++i) {
-            int g = wave * LPT + i; g = g < SEG ? g : SEG - 1;
-            const int sub = g / SEG1, gl = g % SEG1;
-            const char* base = reinterpret_cast<const char*>((gl * RPI < BM ? A : W) + (kt * WK + sub) * BK);
-            __builtin_amdgcn_global_load_lds((const DRF_GLOBAL_AS void*)(base + voff[i]),
-                                             (DRF_LDS_AS void*)(smem + stage * STAGE + sub * STAGE1 + gl * RPI * BK), 16, 0, 0);
-        }
+        static_for<0, LPT>([&](auto ic) { issue_one(ic, kt, stage); });
     };
 
     f32x4 acc[NI][MI];
@@ -314,6 +324,15 @@ gemm_bf16_xl_kernel(const bf16_t* __restrict__ A, const bf16_t* __restrict__ W, 
     constexpr int G = KS * NI;
     constexpr int R = G % 6 == 0 ? 6 : G % 4 == 0 ? 4 : G % 5 == 0 ? 5 : G % 3 == 0 ? 3 : 2, D = R - 1;
     static_assert(G % R == 0 && D < NI && D + MI <= 15, "ring size");
+    // With two stages the copy of tile kt + 2 is not issued as one burst after the barrier of tile kt (72
+    // wave-wide loads that the vector-memory path takes one per ~17 cycles, during which the issuing waves
+    // cannot issue MFMAs) but one instruction per MFMA group: the first HEAD of them in the groups after the
+    // barrier, the remaining TAIL in the first groups of the next tile.  All of them are issued long before
+    // the next barrier, whose vmcnt(0) covers them as before.
+    constexpr int PER = kSpreadPer;                 // copy instructions per MFMA group
+    constexpr int HEAD0 = D * PER < LPT ? D * PER : LPT;
+    constexpr bool kSpread = NS == 2 && WK == 1 && (LPT - HEAD0 + PER - 1) / PER <= G - D;
+    constexpr int HEAD = kSpread ? HEAD0 : LPT, TAIL = LPT - HEAD;
     const int nk = K / (BK * WK);
     u32x4 fa[2][MI], fw[R];
     const uint32_t lds0 = (uint32_t)(uintptr_t)(DRF_LDS_AS unsigned char*)smem_raw;
@@ -359,7 +378,20 @@ gemm_bf16_xl_kernel(const bf16_t* __restrict__ A, const bf16_t* __restrict__ W, 
                 // (the NS - 2 younger tiles may still be in flight; near the end fewer are, so wait for all)
                 if (NS > 2 && kt + NS - 1 < nk) wait_vmcnt<LPT * (NS - 2)>(); else wait_vmcnt<0>();
                 asm volatile("s_waitcnt lgkmcnt(0)\n\ts_barrier" ::: "memory");
-                if (kt + NS < nk) issue(kt + NS, cs);
+                if constexpr (!kSpread) {
+                    if (kt + NS < nk) issue(kt + NS, cs);
+                }
+            }
+            if constexpr (kSpread) {
+                static_for<0, PER>([&](auto uc) {
+                    constexpr int u = decltype(uc)::value;
+                    if constexpr (g >= G - D && (g - (G - D)) * PER + u < HEAD) {
+                        if (kt + NS < nk) issue_one(std::integral_constant<int, (g - (G - D)) * PER + u>{}, kt + NS, cs);
+                    } else if constexpr (g < G - D && g * PER + u < TAIL) {
+                        // the rest of the copy that the previous tile's last groups started: tile kt + 1, into the other stage
+                        if (kt >= 1 && kt + 1 < nk) issue_one(std::integral_constant<int, HEAD + g * PER + u>{}, kt + 1, ns);
+                    }
+                });
             }
             {
                 // on the last tile the positions beyond it read the idle stage: valid LDS, values unused
