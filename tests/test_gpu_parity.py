@@ -313,3 +313,14 @@ def test_sample_edge_cases(torch, drf):
     empty = torch.empty((0, 4, 10, 6), dtype=torch.float32, device="cuda")
     assert den.sample(sd, 0, 2, empty, c[:0]).shape == (0, 4, 10, 6)
     den.close()
+
+
+@pytest.mark.parametrize("steps,batch,guidance", [(50, 24, 3.0), (100, 2, None)])
+def test_sample_with_more_conditioning_rows_than_one_chunk_or_flush(torch, drf, orc, steps, batch, guidance):
+    """The modulation rows of a call are produced per chunk of passes (at most 1024 rows unless one pass has more)
+    and per flush of 64 timestep groups: 50 steps x 48 slot rows = 2400 rows make three chunks, and 100 steps at
+    batch 2 make one chunk of two flushes.  Tiny fp32 DiT of configuration 1, aggressive n = 3, against the oracle."""
+    cfg = I.config(1)
+    cfg["sched"]["steps"] = steps
+    cfg["guidance"] = guidance
+    run_sample(torch, drf, orc, cfg, TOL_F32, mode=I.AGGRESSIVE, n=3, batch=batch, seed=8)
