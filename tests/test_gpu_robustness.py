@@ -99,3 +99,26 @@ def test_second_handle_is_refused_while_the_first_is_in_flight(torch, drf):
     torch.cuda.synchronize()
     assert moved
     a.close(); b.close()
+
+
+def test_more_slots_than_a_launch_covers_is_a_status_code(torch, drf):
+    """Some launches index slots by a grid dimension, so a pass is limited to 65535 slots: beyond that the call
+    returns DRF_ESHAPE before anything is enqueued."""
+    dit = small(I.F32, depth=1, lat_h=2, lat_w=2)
+    den = drf.Denoiser(dit, I.weights(dit, 9))
+    slots = 65536
+    x = torch.zeros((slots, 4, 2, 2), device="cuda")
+    t = torch.zeros((slots,), dtype=torch.int32, device="cuda")
+    out = torch.full_like(x, 7.0)
+    with pytest.raises(drf.DrfError) as ei:
+        den.eps_batched(x, t, t, out=out)
+    assert ei.value.status == -2
+    torch.cuda.synchronize()
+    assert float(out.min()) == 7.0
+    sd = dict(train_steps=1000, beta_start=1e-4, beta_end=0.02, steps=4, eta=0.0)
+    with pytest.raises(drf.DrfError) as ei:
+        den.sample(sd, I.AGGRESSIVE, 2, x[:40000], t[:40000])          # 2 groups x 40000 slots per pass
+    assert ei.value.status == -2
+    ok = den.eps_batched(x[:65535], t[:65535], t[:65535])
+    assert bool(torch.isfinite(ok).all())
+    den.close()
