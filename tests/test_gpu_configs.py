@@ -145,3 +145,34 @@ def test_bf16_determinism_on_the_split_k_and_persistent_paths(torch, drf):
         for _ in range(3):
             assert torch.equal(a, den.eps_batched(x, t, c)), slots
     den.close()
+
+
+def test_config2_shape_under_the_other_samplers(torch, drf):
+    """Configuration 2 at its stated shape under stochastic DDIM (eta = 0.5), the DDPM posterior skip (both with
+    the library's in-kernel noise stream, which the oracle drew with its own generator) and the Euler skip with
+    time shift 3, against stored oracle samples (tests/golden/make_cfg2_samplers.py)."""
+    cfg = I.config(2)
+    dit, B = cfg["dit"], cfg["batch"]
+    recs, name = {}, None
+    for line in open(os.path.join(GOLDEN, "cfg2_samplers_x0.txt")):
+        if line.startswith("#"):
+            f = line.split()
+            if len(f) == 4 and f[2] == "sample":
+                name = (f[1], int(f[3]))
+                recs[name] = []
+            continue
+        recs[name].append(float(line))
+    assert len(recs) == 6
+    den = drf.Denoiser(dit, I.weights(dit, 2))
+    xT, cond = dev(torch, I.latent_noise(dit, B, 2)), dev(torch, I.conditioning(dit, B, 2))
+    for sname, extra in (("ddim_eta0.5", dict(eta=0.5)), ("ddpm", dict(sampler=1)), ("euler_shift3", dict(sampler=2, shift=3.0))):
+        sd = dict(cfg["sched"], **extra)
+        if extra.get("sampler") == 2:
+            got = den.sample(sd, cfg["mode"], cfg["n"], xT, cond)
+        else:
+            got = den.sample_noise(sd, cfg["mode"], cfg["n"], xT, cond, seed=4242, field0=0)
+        got = got.cpu().numpy()
+        for b in (0, 3):
+            want = np.array(recs[(sname, b)]).reshape(got[b].shape)
+            check(got[b][None], want[None], TOL_BF16, "cfg2 %s sample %d" % (sname, b))
+    den.close()
