@@ -358,8 +358,19 @@ gemm_bf16_xl_kernel(const bf16_t* __restrict__ A, const bf16_t* __restrict__ W, 
 #pragma unroll
     for (int t = 1; t < NS - 1; ++t)
         if (t < nk) issue(t, t);
+    // Gated store, all rows of the tile in one slot (the slot length is a multiple of BM): the tile's BN gate
+    // values go to LDS behind the stages, once, and the epilogue reads them from there.  Read from global memory
+    // in the epilogue they would be loaded per 16 x 16 piece, each load waited for on the spot (and, from the
+    // second transposition pass on, behind the stores of the pass before: loads and stores share a counter).
+    const bool gate_lds = e.mode == EPI_STORE_GATED && e.rows_per_slot % BM == 0;
+    float* sgate = reinterpret_cast<float*>(smem_raw + NS * STAGE * 2);
+    if (gate_lds && tid < BN / 4) {
+        const int n = n0 + tid * 4;
+        const float4 gv = *reinterpret_cast<const float4*>(e.gate + (size_t)fast_div(m0, e.rps_magic, e.rps_shift) * e.gate_ld + (n < N ? n : 0));
+        *reinterpret_cast<float4*>(sgate + tid * 4) = gv;
+    }
     if (NS > 2 && nk >= NS - 1) wait_vmcnt<LPT * (NS - 2)>(); else wait_vmcnt<0>();
-    asm volatile("s_barrier" ::: "memory");
+    asm volatile("s_waitcnt lgkmcnt(0)\n\ts_barrier" ::: "memory");
     asm volatile("" ::"v"(warm_val));
     if (NS - 1 < nk) issue(NS - 1, NS - 1);
     static_for<0, D>([&](auto pc) { fetch(pc, a_addr, w_addr); });
@@ -441,7 +452,8 @@ gemm_bf16_xl_kernel(const bf16_t* __restrict__ A, const bf16_t* __restrict__ W, 
     constexpr int WBYTES = (NS * STAGE * 2 - PART) / NWT / 16 * 16; // this wave's private slice of the stages
     unsigned char* wbuf = smem_raw + PART + wl * WBYTES;
     const int mw = m0 + wm * TM, nw = n0 + wn * TN;
-    // bias of this lane's columns, fetched in one batch
+    // bias of this lane's columns, fetched in one batch (kept in registers: reading it from LDS per 16 x 16 piece
+    // like the gate was measured 1 % slower per call)
     float4 bb[NI];
 #pragma unroll
     for (int i = 0; i < NI; ++i) {
@@ -515,8 +527,9 @@ gemm_bf16_xl_kernel(const bf16_t* __restrict__ A, const bf16_t* __restrict__ W, 
         constexpr int RPP = (WBYTES / ROWB) / 16 * 16 < TM ? (WBYTES / ROWB) / 16 * 16 : TM;
         static_assert(RPP >= 16, "LDS slice too small for the bf16 epilogue");
         constexpr int CH = TN / 8, IT = (RPP * CH + 63) / 64;       // 16-byte chunks per row, chunks per lane and pass
-        auto run = [&](auto mode_c) {
+        auto run = [&](auto mode_c, auto gate_lds_c) {
             constexpr int MODE = decltype(mode_c)::value;
+            constexpr bool GLDS = decltype(gate_lds_c)::value;
 #pragma unroll
             for (int j0 = 0; j0 < MI; j0 += RPP / 16) {
 #pragma unroll
@@ -525,7 +538,7 @@ gemm_bf16_xl_kernel(const bf16_t* __restrict__ A, const bf16_t* __restrict__ W, 
                     if (j < MI) {
                         // EPI_STORE_GATED: the gate row of this lane's output row (rows past M use the last one)
                         const float* grow = nullptr;
-                        if constexpr (MODE == EPI_STORE_GATED) {
+                        if constexpr (MODE == EPI_STORE_GATED && !GLDS) {
                             const int mr = mw + j * 16 + l16;
                             grow = e.gate + (size_t)fast_div(mr < M ? mr : M - 1, e.rps_magic, e.rps_shift) * e.gate_ld;
                         }
@@ -534,8 +547,13 @@ gemm_bf16_xl_kernel(const bf16_t* __restrict__ A, const bf16_t* __restrict__ W, 
                             float v0 = acc[i][j][0] + bb[i].x, v1 = acc[i][j][1] + bb[i].y, v2 = acc[i][j][2] + bb[i].z, v3 = acc[i][j][3] + bb[i].w;
                             if (MODE == EPI_STORE_GELU) { v0 = gelu_tanh(v0); v1 = gelu_tanh(v1); v2 = gelu_tanh(v2); v3 = gelu_tanh(v3); }
                             if constexpr (MODE == EPI_STORE_GATED) {
-                                const int ng = nw + i * 16 + 4 * quarter;
-                                const float4 g = *reinterpret_cast<const float4*>(grow + (ng < N ? ng : 0));
+                                float4 g;
+                                if constexpr (GLDS) {
+                                    g = *reinterpret_cast<const float4*>(sgate + wn * TN + i * 16 + 4 * quarter);
+                                } else {
+                                    const int ng = nw + i * 16 + 4 * quarter;
+                                    g = *reinterpret_cast<const float4*>(grow + (ng < N ? ng : 0));
+                                }
                                 v0 *= g.x; v1 *= g.y; v2 *= g.z; v3 *= g.w;
                             }
                             bf16x4 o = { (bf16_t)v0, (bf16_t)v1, (bf16_t)v2, (bf16_t)v3 };
@@ -543,24 +561,36 @@ gemm_bf16_xl_kernel(const bf16_t* __restrict__ A, const bf16_t* __restrict__ W, 
                         }
                     }
                 }
+                // rows back out: all of a pass's LDS reads first (reading is harmless where nothing is stored), then the stores
+                constexpr int kRB = 4;                                  // LDS reads in flight before their stores
 #pragma unroll
-                for (int it = 0; it < IT; ++it) {
-                    const int id = lane + it * 64, rl = id / CH, c = id % CH;
-                    const int m = mw + j0 * 16 + rl, n = nw + c * 8;
-                    if (id < RPP * CH && j0 * 16 + rl < TM && m < M && n < N) {
-                        const size_t off = MODE == EPI_STORE_HEADS ? heads_offset(e, m, n) : (size_t)m * e.ldo + n;
-                        if (n + 8 <= N)
-                            *reinterpret_cast<bf16x8*>((bf16_t*)e.out + off) = *reinterpret_cast<const bf16x8*>(wbuf + rl * ROWB + c * 16);
-                        else                // N is a multiple of 4: the last chunk of a row may be half valid
-                            *reinterpret_cast<bf16x4*>((bf16_t*)e.out + off) = *reinterpret_cast<const bf16x4*>(wbuf + rl * ROWB + c * 16);
+                for (int it0 = 0; it0 < IT; it0 += kRB) {
+                    bf16x8 rv[kRB];
+#pragma unroll
+                    for (int u = 0; u < kRB; ++u) {
+                        const int id = lane + (it0 + u) * 64, idc = id < RPP * CH ? id : RPP * CH - 1;
+                        if (it0 + u < IT) rv[u] = *reinterpret_cast<const bf16x8*>(wbuf + (idc / CH) * ROWB + (idc % CH) * 16);
+                    }
+#pragma unroll
+                    for (int u = 0; u < kRB; ++u) {
+                        const int id = lane + (it0 + u) * 64, rl = id / CH, c = id % CH;
+                        const int m = mw + j0 * 16 + rl, n = nw + c * 8;
+                        if (it0 + u < IT && id < RPP * CH && j0 * 16 + rl < TM && m < M && n < N) {
+                            const size_t off = MODE == EPI_STORE_HEADS ? heads_offset(e, m, n) : (size_t)m * e.ldo + n;
+                            if (n + 8 <= N)
+                                *reinterpret_cast<bf16x8*>((bf16_t*)e.out + off) = rv[u];
+                            else            // N is a multiple of 4: the last chunk of a row may be half valid
+                                *reinterpret_cast<bf16x4*>((bf16_t*)e.out + off) = __builtin_shufflevector(rv[u], rv[u], 0, 1, 2, 3);
+                        }
                     }
                 }
             }
         };
-        if (e.mode == EPI_STORE_GELU) run(std::integral_constant<int, EPI_STORE_GELU>{});
-        else if (e.mode == EPI_STORE_HEADS) run(std::integral_constant<int, EPI_STORE_HEADS>{});
-        else if (e.mode == EPI_STORE_GATED) run(std::integral_constant<int, EPI_STORE_GATED>{});
-        else run(std::integral_constant<int, EPI_STORE>{});
+        if (e.mode == EPI_STORE_GELU) run(std::integral_constant<int, EPI_STORE_GELU>{}, std::false_type{});
+        else if (e.mode == EPI_STORE_HEADS) run(std::integral_constant<int, EPI_STORE_HEADS>{}, std::false_type{});
+        else if (e.mode == EPI_STORE_GATED && gate_lds) run(std::integral_constant<int, EPI_STORE_GATED>{}, std::true_type{});
+        else if (e.mode == EPI_STORE_GATED) run(std::integral_constant<int, EPI_STORE_GATED>{}, std::false_type{});
+        else run(std::integral_constant<int, EPI_STORE>{}, std::false_type{});
     }
 }
 
@@ -619,7 +649,8 @@ drf_status launch_bf16_tile(const bf16_t* A, const bf16_t* W, int M, int N, int 
 template <int BM, int BN, int BK, int NS, int WM, int WN, int WK = 1>
 drf_status launch_bf16_xl(const bf16_t* A, const bf16_t* W, int M, int N, int K, const Epilogue& e, hipStream_t st)
 {
-    constexpr size_t smem = (size_t)NS * WK * (BM + BN) * BK * sizeof(bf16_t);
+    constexpr size_t smem = (size_t)NS * WK * (BM + BN) * BK * sizeof(bf16_t) + BN * sizeof(float);   // stages + gate row
+    static_assert(smem <= 160 * 1024, "LDS of a CU");
     static bool attr_set = false;
     auto kern = gemm_bf16_xl_kernel<BM, BN, BK, NS, WM, WN, WK>;
     if (K % (BK * WK) != 0) DRF_FAIL(DRF_ESHAPE, "bf16 GEMM tile needs K %% %d == 0 (K=%d)", BK * WK, K);
