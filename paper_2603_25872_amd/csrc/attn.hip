@@ -14,6 +14,8 @@ namespace {
 typedef bf16_t bf16x8 __attribute__((ext_vector_type(8)));
 typedef bf16_t bf16x4 __attribute__((ext_vector_type(4)));
 typedef float f32x16 __attribute__((ext_vector_type(16)));
+typedef short s16x4 __attribute__((ext_vector_type(4)));
+#define DRF_LDS_PTR __attribute__((address_space(3)))
 
 constexpr int kKvb = 64;            // kv rows per online-softmax step
 // max of three without the canonicalisation the generic fmaxf lowering adds per operand
@@ -39,22 +41,28 @@ constexpr float kTau = 8.f;         // lazy-rescale headroom of the online softm
 // V^T is stored with the 16 kv rows of each k-chunk permuted to [0-3, 8-11 | 4-7, 12-15]: that is
 // the order in which the score MFMA leaves a lane's P values, so the PV operand is one 16-byte read,
 // and the transposing store of four kv rows of one d is one 8-byte write.
+// VTR: V is staged as stored instead (row-major, contiguous 16-byte pieces like K: coalesced loads and
+// 16-byte LDS writes) and the V^T operand is produced by the LDS transpose read, whose groups of four kv
+// rows are the ones in which the score MFMA leaves a lane's P values.  Cheaper between the steps, dearer
+// inside them (two 8-byte reads per operand): it wins where a chunk is a single step (sequences of up to
+// 256 rows: -3.7 % for those launches) and loses on long sequences (+3 % at 4096 rows).
 // The grid is one-dimensional over work items (query block, head, slot), query block fastest.  With
 // PERSIST a workgroup takes items blockIdx.x, blockIdx.x + gridDim.x, ... and, while it runs the steps
 // of an item's last chunk, already has the next item's Q fragments and first K / V chunk in flight, so
 // only the first item of a workgroup waits for its first loads with nothing else to do.
-template <int KS, int DT, int NW, int KC, int NB, bool PERSIST>
+template <int KS, int DT, int NW, int KC, int NB, bool PERSIST, bool VTR>
 __global__ void __launch_bounds__(NW * 64) attn_bf16_kernel(const AttnArgs a, float scale_log2, int nqb, int n_items)
 {
     static_assert(!PERSIST || NB == 2, "the cross-item prefetch needs two chunk buffers");
     constexpr int NT = NW * 64;
-    constexpr int DK = KS * 16, LDKS = DK + 8, LDV = KC + 8;
-    constexpr int KBUF = KC * LDKS, VBUF = DT * 32 * LDV;
+    // VTR row stride of V: 4 consecutive rows x 32 bytes tile the 32 banks
+    constexpr int DK = KS * 16, LDKS = DK + 8, LDV = VTR ? DT * 32 + 16 : KC + 8;
+    constexpr int KBUF = KC * LDKS, VBUF = VTR ? KC * LDV : DT * 32 * LDV;
     constexpr int MAXK = (KC * (KS * 2) + NT - 1) / NT;                   // 16-byte K pieces of a chunk per thread
-    constexpr int MAXV = ((KC / 4) * (KS * 2) + NT - 1) / NT;             // (4 kv rows x 8 d) V blocks per thread
+    constexpr int MAXV = VTR ? MAXK : ((KC / 4) * (KS * 2) + NT - 1) / NT;  // (4 kv rows x 8 d) V blocks per thread (VTR: pieces as for K)
     extern __shared__ __attribute__((aligned(16))) unsigned char attn_smem[];
     bf16_t* sK = reinterpret_cast<bf16_t*>(attn_smem);                    // [buf][kv][d padded]
-    bf16_t* sVt = sK + NB * KBUF;                                         // [buf][d padded][kv, permuted]
+    bf16_t* sVt = sK + NB * KBUF;                                         // [buf][d padded][kv, permuted]; VTR: [buf][kv][d padded]
     constexpr int LDO = DT * 32 + 8;                                      // row stride of a wave's output tile
     bf16_t* sOut = sVt + NB * VBUF + (threadIdx.x >> 6) * (32 * LDO);     // [wave][32 queries][d padded]
     const int tid = threadIdx.x, lane = tid & 63, wave = tid >> 6, l32 = lane & 31, half = lane >> 5;
@@ -82,7 +90,14 @@ __global__ void __launch_bounds__(NW * 64) attn_bf16_kernel(const AttnArgs a, fl
             f[ks] = dd < d ? *reinterpret_cast<const bf16x8*>(it.Q + (size_t)qc * a.ldq + dd) : zero8;
         }
     };
-    int item = blockIdx.x;
+    // Workgroup ids are dealt round-robin over the 8 XCDs, each with its own L2.  The query blocks of one
+    // (slot, head) read the same K / V rows, so position v of the launch order takes the item that puts
+    // consecutive items on one XCD: its L2 then fetches a head's K / V once, not once per XCD.
+    auto item_at = [&](int v) {
+        const int q8 = n_items >> 3, rem = n_items & 7, xcd = v & 7;
+        return nqb > 1 ? xcd * q8 + (xcd < rem ? xcd : rem) + (v >> 3) : v;
+    };
+    int vpos = blockIdx.x, item = item_at(vpos);
     Item cur = locate(item);
 
     // zero the padding that loads never touch: K columns [d, DK), V^T rows [d, DT*32)
@@ -91,8 +106,13 @@ __global__ void __launch_bounds__(NW * 64) attn_bf16_kernel(const AttnArgs a, fl
     // then accumulates the softmax denominator there for free.
     const bool ones_row = d < DT * 32;
     __syncthreads();
-    if (ones_row)
-        for (int i = tid; i < NB * LDV; i += NT) sVt[(i / LDV) * VBUF + d * LDV + i % LDV] = (bf16_t)1.f;
+    if (ones_row) {
+        if constexpr (VTR) {
+            for (int i = tid; i < NB * KC; i += NT) sVt[(i / KC) * VBUF + (i % KC) * LDV + d] = (bf16_t)1.f;
+        } else {
+            for (int i = tid; i < NB * LDV; i += NT) sVt[(i / LDV) * VBUF + d * LDV + i % LDV] = (bf16_t)1.f;
+        }
+    }
 
     bf16x8 qf[KS];
     load_q(cur, qf);
@@ -103,7 +123,7 @@ __global__ void __launch_bounds__(NW * 64) attn_bf16_kernel(const AttnArgs a, fl
     // K: consecutive threads take consecutive 16-byte pieces of a row (coalesced loads, 16-byte LDS
     // writes).  V: a thread takes 4 consecutive kv rows of one 8-wide d piece and writes, for each
     // of the 8 d, the 4 kv values as one 8-byte piece of the V^T row.
-    bf16x8 rk[MAXK], rv[MAXV][4];
+    bf16x8 rk[MAXK], rv[MAXV][VTR ? 1 : 4];
     auto fetch = [&](const Item& it, int kv0) {
 #pragma unroll
         for (int c = 0; c < MAXK; ++c) {
@@ -111,14 +131,23 @@ __global__ void __launch_bounds__(NW * 64) attn_bf16_kernel(const AttnArgs a, fl
             rk[c] = zero8;
             if (id < nch && kv0 + r < a.Nk) rk[c] = *reinterpret_cast<const bf16x8*>(it.Kp + (size_t)(kv0 + r) * a.ldk + cc * 8);
         }
+        if constexpr (VTR) {
 #pragma unroll
-        for (int c = 0; c < MAXV; ++c) {
-            const int id = tid + c * NT, g4 = id % (KC / 4), cc = id / (KC / 4);
+            for (int c = 0; c < MAXV; ++c) {
+                const int id = tid + c * NT, r = id / dch, cc = id % dch;
+                rv[c][0] = zero8;
+                if (id < nch && kv0 + r < a.Nk) rv[c][0] = *reinterpret_cast<const bf16x8*>(it.Vp + (size_t)(kv0 + r) * a.ldk + cc * 8);
+            }
+        } else {
 #pragma unroll
-            for (int j = 0; j < 4; ++j) {
-                rv[c][j] = zero8;
-                if (id < nvb && kv0 + 4 * g4 + j < a.Nk)
-                    rv[c][j] = *reinterpret_cast<const bf16x8*>(it.Vp + (size_t)(kv0 + 4 * g4 + j) * a.ldk + cc * 8);
+            for (int c = 0; c < MAXV; ++c) {
+                const int id = tid + c * NT, g4 = id % (KC / 4), cc = id / (KC / 4);
+#pragma unroll
+                for (int j = 0; j < 4; ++j) {
+                    rv[c][j] = zero8;
+                    if (id < nvb && kv0 + 4 * g4 + j < a.Nk)
+                        rv[c][j] = *reinterpret_cast<const bf16x8*>(it.Vp + (size_t)(kv0 + 4 * g4 + j) * a.ldk + cc * 8);
+                }
             }
         }
     };
@@ -130,17 +159,25 @@ __global__ void __launch_bounds__(NW * 64) attn_bf16_kernel(const AttnArgs a, fl
             const int id = tid + c * NT, r = id / dch, cc = id % dch;
             if (id < nch) *reinterpret_cast<bf16x8*>(bk + r * LDKS + cc * 8) = rk[c];
         }
+        if constexpr (VTR) {
 #pragma unroll
-        for (int c = 0; c < MAXV; ++c) {
-            const int id = tid + c * NT, g4 = id % (KC / 4), cc = id / (KC / 4);
-            // kv rows 4 g4 .. 4 g4 + 3 of the chunk: position of row r16 inside its 16-row group is
-            // 8 * ((r16 >> 2) & 1) + (r16 & 3) + 4 * (r16 >> 3)
-            const int k4 = g4 & 3, pos = 16 * (g4 >> 2) + 8 * (k4 & 1) + 4 * (k4 >> 1);
-            if (id < nvb) {
+            for (int c = 0; c < MAXV; ++c) {
+                const int id = tid + c * NT, r = id / dch, cc = id % dch;
+                if (id < nch) *reinterpret_cast<bf16x8*>(bv + r * LDV + cc * 8) = rv[c][0];
+            }
+        } else {
 #pragma unroll
-                for (int e = 0; e < 8; ++e) {
-                    const bf16x4 w = { rv[c][0][e], rv[c][1][e], rv[c][2][e], rv[c][3][e] };
-                    *reinterpret_cast<bf16x4*>(bv + (cc * 8 + e) * LDV + pos) = w;
+            for (int c = 0; c < MAXV; ++c) {
+                const int id = tid + c * NT, g4 = id % (KC / 4), cc = id / (KC / 4);
+                // kv rows 4 g4 .. 4 g4 + 3 of the chunk: position of row r16 inside its 16-row group is
+                // 8 * ((r16 >> 2) & 1) + (r16 & 3) + 4 * (r16 >> 3)
+                const int k4 = g4 & 3, pos = 16 * (g4 >> 2) + 8 * (k4 & 1) + 4 * (k4 >> 1);
+                if (id < nvb) {
+#pragma unroll
+                    for (int e = 0; e < 8; ++e) {
+                        const bf16x4 w = { rv[c][0][e], rv[c][1][e], rv[c][2][e], rv[c][3][e] };
+                        *reinterpret_cast<bf16x4*>(bv + (cc * 8 + e) * LDV + pos) = w;
+                    }
                 }
             }
         }
@@ -166,13 +203,24 @@ __global__ void __launch_bounds__(NW * 64) attn_bf16_kernel(const AttnArgs a, fl
                 s[t] = __builtin_amdgcn_mfma_f32_32x32x16_bf16(kf[t][ks], qf[ks], ks == 0 ? zero16 : s[t], 0, 0, 0);
         }
         bf16x8 vf[2][2][DT];
+        // VTR: the 16 lanes of a group point at 4 kv rows x 16 d (8 bytes each) and lane i receives column i of
+        // the 4 rows; two reads per operand: kv rows 16 c + 4 half + (0..3) and the same + 8, the two groups of
+        // four kv rows that a lane's P values of k-chunk c belong to
+        const bf16_t* vl = bv + (row0 + 4 * half + ((lane & 15) >> 2)) * LDV + (l32 & 16) + 4 * (lane & 3);
 #pragma unroll
         for (int t = 0; t < 2; ++t)
 #pragma unroll
             for (int c = 0; c < 2; ++c)
 #pragma unroll
-                for (int tt = 0; tt < DT; ++tt)
-                    vf[t][c][tt] = *reinterpret_cast<const bf16x8*>(bv + (tt * 32 + l32) * LDV + row0 + t * 32 + 16 * c + 8 * half);
+                for (int tt = 0; tt < DT; ++tt) {
+                    if constexpr (VTR) {
+                        const s16x4 lo = __builtin_amdgcn_ds_read_tr16_b64_v4i16((DRF_LDS_PTR s16x4*)(vl + (t * 32 + 16 * c) * LDV + tt * 32));
+                        const s16x4 hi = __builtin_amdgcn_ds_read_tr16_b64_v4i16((DRF_LDS_PTR s16x4*)(vl + (t * 32 + 16 * c + 8) * LDV + tt * 32));
+                        vf[t][c][tt] = __builtin_bit_cast(bf16x8, __builtin_shufflevector(lo, hi, 0, 1, 2, 3, 4, 5, 6, 7));
+                    } else {
+                        vf[t][c][tt] = *reinterpret_cast<const bf16x8*>(bv + (tt * 32 + l32) * LDV + row0 + t * 32 + 16 * c + 8 * half);
+                    }
+                }
         __builtin_amdgcn_sched_barrier(0);
         // register r of s[t] holds kv row t*32 + 8*(r/4) + 4*half + r%4 of the step
         if (kv0 + kKvb > a.Nk) {            // ragged last step: rows past the end do not take part
@@ -236,8 +284,9 @@ __global__ void __launch_bounds__(NW * 64) attn_bf16_kernel(const AttnArgs a, fl
     __syncthreads();
     int buf = 0;
     for (;;) {
-        const int nxt = item + (int)gridDim.x;
-        const bool has_next = PERSIST && nxt < n_items;
+        const int vnxt = vpos + (int)gridDim.x;
+        const bool has_next = PERSIST && vnxt < n_items;
+        const int nxt = has_next ? item_at(vnxt) : item;
         Item np = cur;
 #pragma unroll
         for (int t = 0; t < DT; ++t)
@@ -312,6 +361,7 @@ __global__ void __launch_bounds__(NW * 64) attn_bf16_kernel(const AttnArgs a, fl
             }
         }
         if (!has_next) break;
+        vpos = vnxt;
         item = nxt;
         cur = np;
     }
@@ -378,13 +428,13 @@ __global__ void __launch_bounds__(kF32Threads) attn_f32_kernel(const AttnArgs a,
     }
 }
 
-template <int KS, int DT, int NW, int KC, int NB, bool PERSIST = false>
+template <int KS, int DT, int NW, int KC, int NB, bool PERSIST = false, bool VTR = false>
 drf_status launch_bf16_cfg(const AttnArgs& a, float scale_log2, hipStream_t st)
 {
-    constexpr int LDKS = KS * 16 + 8, LDV = KC + 8;
-    constexpr size_t smem = ((size_t)NB * (KC * LDKS + DT * 32 * LDV) + (size_t)NW * 32 * (DT * 32 + 8)) * sizeof(bf16_t);
+    constexpr int LDKS = KS * 16 + 8, LDV = VTR ? DT * 32 + 16 : KC + 8;
+    constexpr size_t smem = ((size_t)NB * (KC * LDKS + (VTR ? KC : DT * 32) * LDV) + (size_t)NW * 32 * (DT * 32 + 8)) * sizeof(bf16_t);
     static_assert(smem <= 160 * 1024 && smem % 16 == 0, "LDS budget");
-    auto kern = attn_bf16_kernel<KS, DT, NW, KC, NB, PERSIST>;
+    auto kern = attn_bf16_kernel<KS, DT, NW, KC, NB, PERSIST, VTR>;
     static bool attr_set = false;
     if (!attr_set) {
         DRF_HIP(hipFuncSetAttribute(reinterpret_cast<const void*>(kern), hipFuncAttributeMaxDynamicSharedMemorySize, (int)smem));
@@ -412,8 +462,8 @@ drf_status launch_bf16_inst(const AttnArgs& a, float scale_log2, hipStream_t st)
             // more items than workgroups that fit the chip at once: persistent workgroups hide each next
             // item's first loads; otherwise the plain kernel (fewer registers) is the faster one
             const long long n_items = (long long)((a.Nq + 255) / 256) * a.heads * a.slots;
-            if (n_items > kPersistGroups) return launch_bf16_cfg<KS, DT, 8, 64, 2, true>(a, scale_log2, st);
-            return launch_bf16_cfg<KS, DT, 8, 64, 2>(a, scale_log2, st);
+            if (n_items > kPersistGroups) return launch_bf16_cfg<KS, DT, 8, 64, 2, true, true>(a, scale_log2, st);
+            return launch_bf16_cfg<KS, DT, 8, 64, 2, false, true>(a, scale_log2, st);
         }
         return launch_bf16_cfg<KS, DT, 8, 128, 2>(a, scale_log2, st);
     }
