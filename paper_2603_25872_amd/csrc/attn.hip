@@ -103,12 +103,14 @@ __global__ void __launch_bounds__(NW * 64) attn_bf16_kernel(const AttnArgs a, fl
     // zero the padding that loads never touch: K columns [d, DK), V^T rows [d, DT*32)
     for (int i = tid; i < NB * (KBUF + VBUF) / 8; i += NT) reinterpret_cast<bf16x8*>(sK)[i] = zero8;
     // When the head width leaves a padding row in O^T, V^T row d is set to ones: the PV MFMA
-    // then accumulates the softmax denominator there for free.
+    // then accumulates the softmax denominator there for free.  (VTR: the last padding column of V, so that the
+    // accumulator register that ends up holding the denominator is known at compile time: -4.5 % for the
+    // 256-row launches; the same move in the V^T layout made the 4096-row launches 3.5 % slower.)
     const bool ones_row = d < DT * 32;
     __syncthreads();
     if (ones_row) {
         if constexpr (VTR) {
-            for (int i = tid; i < NB * KC; i += NT) sVt[(i / KC) * VBUF + (i % KC) * LDV + d] = (bf16_t)1.f;
+            for (int i = tid; i < NB * KC; i += NT) sVt[(i / KC) * VBUF + (i % KC) * LDV + DT * 32 - 1] = (bf16_t)1.f;
         } else {
             for (int i = tid; i < NB * LDV; i += NT) sVt[(i / LDV) * VBUF + d * LDV + i % LDV] = (bf16_t)1.f;
         }
@@ -325,7 +327,12 @@ __global__ void __launch_bounds__(NW * 64) attn_bf16_kernel(const AttnArgs a, fl
         }
         // denominator: from the ones row (kept by the lanes of one half) or the two halves' partial sums
         float l_tot;
-        if (ones_row) {
+        if (ones_row && VTR) {
+            // O^T row 31 of the last row tile: register 4 * (31 >> 3) + (31 & 3) = 15 of the lanes of half (31 >> 2) & 1 = 1
+            const float mine = o[DT - 1][15];
+            const float other = __shfl_xor(mine, 32, 64);
+            l_tot = half == 1 ? mine : other;
+        } else if (ones_row) {
             const int tt = d >> 5, lr = d & 31, r = 4 * (lr >> 3) + (lr & 3), owner = (lr >> 2) & 1;
             float mine = 0.f;
 #pragma unroll
