@@ -150,7 +150,7 @@ def main():
         os_ = torch.empty_like(xs)
         table = []
         for m_, mname in ((I.CONSERVATIVE, "conservative"), (I.AGGRESSIVE, "aggressive")):
-            for k in (1, 2, 4, 8):
+            for k in (1, 2, 3, 4, 8):
                 for _ in range(max(args.warmup, 1)):
                     den.sample(cfg["sched"], m_, k, xs, cs, ns, cfg["guidance"] or 0.0, out=os_)
                 torch.cuda.synchronize()
