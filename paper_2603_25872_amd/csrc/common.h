@@ -122,8 +122,11 @@ void make_fast_div(int d, uint32_t* magic, int* shift);
 void set_rows_per_slot(Epilogue* e, int rows_per_slot);
 // C[M][N] = A[M][K] . W[N][K]^T, then the epilogue.  bf16: K % 64 == 0.
 // variant 0: the tile shape is chosen from the problem size; > 0 forces one (measurement and tile tests).
+// splitk_scratch: gemm_splitk_scratch_bytes() of device memory, or NULL; with it, problems of few tiles and a long
+// K are split across workgroups (variant 10 forces the 128 x 128 tile, split when the rule allows).
 drf_status launch_gemm_bf16(const bf16_t* A, const bf16_t* W, int M, int N, int K, const Epilogue& e, hipStream_t st,
-                            int variant = 0);
+                            int variant = 0, float* splitk_scratch = nullptr);
+size_t gemm_splitk_scratch_bytes();
 drf_status launch_gemm_f32(const float* A, const float* W, int M, int N, int K, const Epilogue& e, hipStream_t st);
 
 struct AttnArgs {

@@ -32,6 +32,7 @@ struct Workspace {
     float *resid = nullptr, *mod = nullptr, *cact32 = nullptr, *cscratch = nullptr;
     void *hbuf = nullptr, *qkv = nullptr, *mid = nullptr, *ybuf = nullptr, *ybuf2 = nullptr, *cact = nullptr;
     void *xkv = nullptr, *ctx_act = nullptr;    // cross-attention K/V cache [L][rows][ctx_len][2D] and its staging
+    float* skpart = nullptr;                    // partial tiles of the split-K GEMM (bf16 path), or NULL: no split
 };
 
 // Arguments that fix the launch sequence of a drf_sample call, and the graph captured for them.
@@ -210,6 +211,7 @@ drf_status ensure_workspace(drf_denoiser* d, int slots, hipStream_t st)
     dev_free(d, &w.resid); dev_free(d, &w.hbuf); dev_free(d, &w.qkv); dev_free(d, &w.mid); dev_free(d, &w.ybuf); dev_free(d, &w.ybuf2);
     const WorkspaceBytes b = workspace_bytes(d, (size_t)slots, 0, 0);
     drf_status rc;
+    if (d->bf16 && !w.skpart && (rc = dev_alloc(d, (void**)&w.skpart, gemm_splitk_scratch_bytes())) != DRF_OK) return rc;
     if ((rc = dev_alloc(d, (void**)&w.resid, b.resid)) != DRF_OK) return rc;
     if ((rc = dev_alloc(d, &w.hbuf, b.hbuf)) != DRF_OK) return rc;
     if ((rc = dev_alloc(d, &w.qkv, b.qkv)) != DRF_OK) return rc;
@@ -255,11 +257,11 @@ drf_status ensure_ctx(drf_denoiser* d, int rows, hipStream_t st)
     return DRF_OK;
 }
 
-drf_status gemm(drf_denoiser* d, const void* A, const LinearW& w, int M, Epilogue e, hipStream_t st)
+drf_status gemm(drf_denoiser* d, const void* A, const LinearW& w, int M, Epilogue e, hipStream_t st, float* splitk_scratch = nullptr)
 {
     e.bias = w.b;
     ProfScope ps(d, st, DRF_PROF_GEMM, 2.0 * M * (double)w.N * w.K);
-    if (d->bf16) return launch_gemm_bf16((const bf16_t*)A, w.w16, M, w.N, w.K, e, st);
+    if (d->bf16) return launch_gemm_bf16((const bf16_t*)A, w.w16, M, w.N, w.K, e, st, 0, splitk_scratch);
     return launch_gemm_f32((const float*)A, w.w32, M, w.N, w.K, e, st);
 }
 
@@ -431,11 +433,11 @@ drf_status forward(drf_denoiser* d, const Workspace& ws, const float* x, const S
         if ((rc = ln(mrow + 3 * D, mrow + 4 * D, nm, f32 || last)) != DRF_OK) return rc;
         if ((rc = gemm(d, ws.hbuf, b.fc1, M, with_warm(epi_store(ws.mid, dm.R * D, f32, true), f32 ? nullptr : &b.fc2), st)) != DRF_OK) return rc;
         if (f32 || last) {
-            if ((rc = gemm(d, ws.mid, b.fc2, M, epi_resid(ws.resid, D, mrow + 5 * D, nm, dm.T), st)) != DRF_OK) return rc;
+            if ((rc = gemm(d, ws.mid, b.fc2, M, epi_resid(ws.resid, D, mrow + 5 * D, nm, dm.T), st, ws.skpart)) != DRF_OK) return rc;
         } else {
             // the attention output may still be pending in ybuf: the MLP output goes to the second buffer
             void* yo = pend1 ? ws.ybuf2 : ws.ybuf;
-            if ((rc = gemm(d, ws.mid, b.fc2, M, with_warm(epi_gated(yo, D, mrow + 5 * D, nm, dm.T), &d->blk[l + 1].qkv), st)) != DRF_OK) return rc;
+            if ((rc = gemm(d, ws.mid, b.fc2, M, with_warm(epi_gated(yo, D, mrow + 5 * D, nm, dm.T), &d->blk[l + 1].qkv), st, ws.skpart)) != DRF_OK) return rc;
             (pend1 ? pend2 : pend1) = (const bf16_t*)yo;
         }
     }
@@ -509,6 +511,10 @@ drf_status carve_static(const drf_denoiser* d, int slots, Workspace* ws)
     if (off > (size_t)DRF_STATIC_SCRATCH_BYTES)
         DRF_FAIL(DRF_ESHAPE, "a pass of %d slots needs %zu bytes of scratch; the static array holds %zu", slots, off,
                  (size_t)DRF_STATIC_SCRATCH_BYTES);
+    // the split-K partial tiles only where the array has room left for them (without: the unsplit GEMM, same results
+    // up to the order of the k-sums)
+    ws->skpart = nullptr;
+    if (d->bf16 && off + gemm_splitk_scratch_bytes() <= (size_t)DRF_STATIC_SCRATCH_BYTES) ws->skpart = (float*)take(gemm_splitk_scratch_bytes());
     return DRF_OK;
 }
 
@@ -1072,7 +1078,12 @@ extern "C" drf_status drf_probe_gemm_bf16(const void* A, const void* W, int M, i
     if (!A || !W || !out_bf16 || !bias || M < 0 || N < 0 || K < 0) DRF_FAIL(DRF_EINVAL, "bad argument");
     Epilogue e{};
     e.mode = EPI_STORE; e.out = out_bf16; e.ldo = N; e.out_f32 = 0; e.bias = bias;
-    return launch_gemm_bf16((const bf16_t*)A, (const bf16_t*)W, M, N, K, e, (hipStream_t)hip_stream, variant);
+    // variant 10 (the 128 x 128 tile, K split across workgroups where the rule allows): partial tiles in a buffer
+    // that the probe allocates once per process and keeps
+    static float* probe_splitk = nullptr;
+    if (variant == 10 && !probe_splitk) DRF_HIP(hipMalloc((void**)&probe_splitk, gemm_splitk_scratch_bytes()));
+    return launch_gemm_bf16((const bf16_t*)A, (const bf16_t*)W, M, N, K, e, (hipStream_t)hip_stream, variant,
+                            variant == 10 ? probe_splitk : nullptr);
 }
 
 extern "C" drf_status drf_probe_attn_bf16(const void* qkv, void* out, int slots, int tokens, int heads, int head_dim,

@@ -218,11 +218,21 @@ typedef float f32x4 __attribute__((ext_vector_type(4)));
 // copy instructions issued per MFMA group by the in-loop copy of the two-stage kernels (1: measured best; 2, 3 and
 // the whole copy at once are 0.8 % slower per call, one every other group lands too late: 3 % slower)
 constexpr int kSpreadPer = 1;
+// split K across workgroups: at most this many workgroups per launch (one round of the GPU's CUs), and only
+// when the problem has at least this many 64-wide k-tiles (shorter ones do not repay the reduction launch)
+constexpr int kSplitKMaxGroups = 256, kSplitKMinKTiles = 36;
 
-template <int BM, int BN, int BK, int NS, int WM, int WN, int WK = 1>
+//  - SK (split K across workgroups, for problems with few tiles and a long K: the out-projection of the MLP at
+//    one or two samples per pass): tiles_n counts sk.splits column-tile rows, workgroup (tm, tn) takes k-range
+//    tn / sk.tiles_n of column tile tn % sk.tiles_n and leaves its fp32 partial tile in sk.part
+//    ([split][tiles_m * BM][sk.tiles_n * BN], padded, so no bounds are needed); splitk_reduce_kernel adds the
+//    partial tiles in a fixed order and applies the epilogue.
+struct SplitK { int splits, tiles_n, ksub; float* part; };
+
+template <int BM, int BN, int BK, int NS, int WM, int WN, int WK = 1, bool SK = false>
 __global__ void __launch_bounds__(WM * WN * WK * 64)
 gemm_bf16_xl_kernel(const bf16_t* __restrict__ A, const bf16_t* __restrict__ W, int M, int N, int K, const Epilogue e,
-                    int tiles_m, int tiles_n)
+                    int tiles_m, int tiles_n, const SplitK sk)
 {
     // WK > 1: the waves form WK groups that share the output tile and split K between them (group g
     // takes the k-tiles g, g + WK, ...); the groups' partial sums are added through LDS before the
@@ -242,7 +252,9 @@ gemm_bf16_xl_kernel(const bf16_t* __restrict__ A, const bf16_t* __restrict__ W, 
     const int per_group = GROUP_M * tiles_n, group = idx / per_group, first_m = group * GROUP_M;
     const int gsz = tiles_m - first_m < GROUP_M ? tiles_m - first_m : GROUP_M;
     const int tm = first_m + (idx % per_group) % gsz, tn = (idx % per_group) / gsz;
-    const int m0 = tm * BM, n0 = tn * BN;
+    const int split = SK ? tn / sk.tiles_n : 0;
+    const int m0 = tm * BM, n0 = (SK ? tn - split * sk.tiles_n : tn) * BN;
+    if constexpr (SK) { A += split * sk.ksub; W += split * sk.ksub; }   // row stride stays K
 
     const int tid = threadIdx.x, lane = tid & 63;
     const int wave = __builtin_amdgcn_readfirstlane(tid >> 6);      // wave-uniform, kept in a scalar register
@@ -333,7 +345,7 @@ gemm_bf16_xl_kernel(const bf16_t* __restrict__ A, const bf16_t* __restrict__ W, 
     constexpr int HEAD0 = D * PER < LPT ? D * PER : LPT;
     constexpr bool kSpread = NS == 2 && WK == 1 && (LPT - HEAD0 + PER - 1) / PER <= G - D;
     constexpr int HEAD = kSpread ? HEAD0 : LPT, TAIL = LPT - HEAD;
-    const int nk = K / (BK * WK);
+    const int nk = (SK ? sk.ksub : K) / (BK * WK);
     u32x4 fa[2][MI], fw[R];
     const uint32_t lds0 = (uint32_t)(uintptr_t)(DRF_LDS_AS unsigned char*)smem_raw;
     uint32_t a_addr[KS], w_addr[KS];                // byte addresses of this lane's fragments in stage 0
@@ -428,6 +440,17 @@ gemm_bf16_xl_kernel(const bf16_t* __restrict__ A, const bf16_t* __restrict__ W, 
     }
     wait_lgkmcnt<0>();                              // the last tile's look-ahead reads
 
+    if constexpr (SK) {
+        // partial tile, straight from the accumulators: acc[i][j][r] is (m = j*16 + l16, n = i*16 + 4*quarter + r)
+        static_assert(WK == 1, "split K across workgroups or across wave groups, not both");
+        float* pt = sk.part + ((size_t)split * tiles_m * BM + m0 + wm * TM) * ((size_t)sk.tiles_n * BN) + n0 + wn * TN;
+#pragma unroll
+        for (int i = 0; i < NI; ++i)
+#pragma unroll
+            for (int j = 0; j < MI; ++j)
+                *reinterpret_cast<f32x4*>(pt + (size_t)(j * 16 + l16) * ((size_t)sk.tiles_n * BN) + i * 16 + 4 * quarter) = acc[i][j];
+        return;
+    }
     // ---- epilogue through LDS: acc[i][j][r] is (m = j*16 + l16, n = i*16 + 4*quarter + r) of the wave tile
     __syncthreads();
     constexpr int PART = (WK - 1) * NWT * TM * TN * 4;              // partial sums of the other K groups
@@ -594,6 +617,22 @@ gemm_bf16_xl_kernel(const bf16_t* __restrict__ A, const bf16_t* __restrict__ W, 
     }
 }
 
+// Sum of the split-K partial tiles (fixed order: deterministic), then the epilogue; one thread per 4 columns.
+__global__ void __launch_bounds__(256)
+splitk_reduce_kernel(const float* __restrict__ part, int splits, size_t split_stride, int ldp, int M, int N, const Epilogue e)
+{
+    const int n4 = N / 4, id = blockIdx.x * 256 + threadIdx.x;
+    if (id >= M * n4) return;
+    const int m = id / n4, n = (id - m * n4) * 4;
+    const float* p = part + (size_t)m * ldp + n;
+    float4 v = *reinterpret_cast<const float4*>(p);
+    for (int s2 = 1; s2 < splits; ++s2) {
+        const float4 u = *reinterpret_cast<const float4*>(p + (size_t)s2 * split_stride);
+        v.x += u.x; v.y += u.y; v.z += u.z; v.w += u.w;
+    }
+    epilogue4(e, m, n, v.x, v.y, v.z, v.w);
+}
+
 // ------------------------------------------------------------------------ fp32
 // 64 x 64 x 16 tile, 256 threads, 4 x 4 outputs per thread (columns n consecutive).
 __global__ void __launch_bounds__(256)
@@ -659,15 +698,42 @@ drf_status launch_bf16_xl(const bf16_t* A, const bf16_t* W, int M, int N, int K,
         attr_set = true;
     }
     const int tiles_m = (M + BM - 1) / BM, tiles_n = (N + BN - 1) / BN;
-    hipLaunchKernelGGL(kern, dim3(tiles_m * tiles_n), dim3(WM * WN * WK * 64), smem, st, A, W, M, N, K, e, tiles_m, tiles_n);
+    hipLaunchKernelGGL(kern, dim3(tiles_m * tiles_n), dim3(WM * WN * WK * 64), smem, st, A, W, M, N, K, e, tiles_m, tiles_n, SplitK{});
+    DRF_HIP(hipGetLastError());
+    return DRF_OK;
+}
+
+// Split-K form of the 128 x 128 tile: `splits` workgroups per output tile, partial tiles in `part`
+// (splits * tiles * 128 * 128 floats), then the reduction with the epilogue.
+drf_status launch_bf16_splitk(const bf16_t* A, const bf16_t* W, int M, int N, int K, const Epilogue& e, hipStream_t st,
+                              int splits, float* part)
+{
+    constexpr int BM = 128, BN = 128, BK = 64;
+    constexpr size_t smem = (size_t)2 * (BM + BN) * BK * sizeof(bf16_t) + BN * sizeof(float);
+    static bool attr_set = false;
+    auto kern = gemm_bf16_xl_kernel<BM, BN, BK, 2, 2, 2, 1, true>;
+    if (!attr_set) {
+        DRF_HIP(hipFuncSetAttribute(reinterpret_cast<const void*>(kern), hipFuncAttributeMaxDynamicSharedMemorySize, (int)smem));
+        attr_set = true;
+    }
+    const int tiles_m = (M + BM - 1) / BM, tiles_n = (N + BN - 1) / BN;
+    SplitK sk{ splits, tiles_n, K / splits, part };
+    hipLaunchKernelGGL(kern, dim3(tiles_m * tiles_n * splits), dim3(256), smem, st, A, W, M, N, K, e, tiles_m, tiles_n * splits, sk);
+    DRF_HIP(hipGetLastError());
+    const int ldp = tiles_n * BN;
+    const long long quads = (long long)M * (N / 4);
+    hipLaunchKernelGGL(splitk_reduce_kernel, dim3((unsigned)((quads + 255) / 256)), dim3(256), 0, st, part, splits,
+                       (size_t)tiles_m * BM * ldp, ldp, M, N, e);
     DRF_HIP(hipGetLastError());
     return DRF_OK;
 }
 
 }  // namespace
 
+size_t gemm_splitk_scratch_bytes() { return (size_t)kSplitKMaxGroups * 128 * 128 * sizeof(float); }
+
 drf_status launch_gemm_bf16(const bf16_t* A, const bf16_t* W, int M, int N, int K, const Epilogue& e, hipStream_t st,
-                            int variant)
+                            int variant, float* splitk_scratch)
 {
     if (M == 0 || N == 0) return DRF_OK;
     if (K % 64 != 0 || N % 4 != 0 || e.ldo % 4 != 0) DRF_FAIL(DRF_ESHAPE, "bf16 GEMM needs K %% 64 == 0 and N %% 4 == 0 (M=%d N=%d K=%d)", M, N, K);
@@ -695,6 +761,16 @@ drf_status launch_gemm_bf16(const bf16_t* A, const bf16_t* W, int M, int N, int 
             // one small tile per CU: let two wave groups split K inside the block
             if (v == 7 && K % 128 == 0 && K >= 1024) v = 8;
         }
+    }
+    // Few 128 x 128 tiles and a long K (the MLP's out-projection at one or two samples per pass: 36 tiles of 72
+    // k-tiles on 256 CUs): split K over as many workgroups as fit one round, the k-tiles dividing evenly.
+    if (v == 10) v = 5;
+    if ((v == 5 || v == 1) && (variant == 0 || variant == 10) && splitk_scratch && K / 64 >= kSplitKMinKTiles) {
+        const int tiles = ((M + 127) / 128) * ((N + 127) / 128), nk = K / 64;
+        int splits = 0;
+        for (int s2 = 2; s2 <= 8 && s2 * tiles <= kSplitKMaxGroups; ++s2)
+            if (nk % s2 == 0 && nk / s2 >= 4) splits = s2;
+        if (splits) return launch_bf16_splitk(A, W, M, N, K, e, st, splits, splitk_scratch);
     }
     switch (v) {
     case 2: return launch_bf16_xl<256, 288, 64, 2, 4, 2>(A, W, M, N, K, e, st);

@@ -45,6 +45,24 @@ def test_gemm_bf16_every_tile_shape(torch, drf, orc, variant, M, N, K):
     assert err < 6e-3, err                       # bf16 rounding of the stored result: 2^-8 relative at worst
 
 
+@pytest.mark.parametrize("M,N,K", [(512, 1152, 4608), (300, 292, 2304), (1024, 576, 2304), (130, 132, 2560)])
+def test_gemm_bf16_split_k(torch, drf, orc, M, N, K):
+    """Few 128 x 128 tiles and a long K: K is split across workgroups and the partial tiles are added by a second
+    launch (6, 6, 3 and 8 splits here); same tolerance as the unsplit tile, whose result it must also track closely."""
+    rng = np.random.default_rng(M + N + K)
+    A = bf16_round(torch, rng.standard_normal((M, K)))
+    W = bf16_round(torch, rng.standard_normal((N, K)) * 0.1)
+    b = rng.standard_normal(N).astype(np.float32)
+    out = drf.probe_gemm_bf16(A.cuda(), W.cuda(), torch.from_numpy(b).cuda(), variant=10).float().cpu().numpy()
+    again = drf.probe_gemm_bf16(A.cuda(), W.cuda(), torch.from_numpy(b).cuda(), variant=10).float().cpu().numpy()
+    assert np.array_equal(out, again)            # fixed summation order
+    whole = drf.probe_gemm_bf16(A.cuda(), W.cuda(), torch.from_numpy(b).cuda(), variant=5).float().cpu().numpy()
+    want = orc.linear(A.float().numpy(), W.float().numpy(), b)
+    scale = np.abs(want).max()
+    assert np.abs(out - want).max() / scale < 6e-3
+    assert np.abs(out - whole).max() / scale < 6e-3   # both are bf16 roundings of nearly the same fp32 sums
+
+
 def test_gemm_bf16_rejects_bad_k(torch, drf):
     A = torch.zeros((64, 72), dtype=torch.bfloat16, device="cuda")
     W = torch.zeros((64, 72), dtype=torch.bfloat16, device="cuda")

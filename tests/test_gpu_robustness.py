@@ -82,12 +82,19 @@ def test_second_handle_is_refused_while_the_first_is_in_flight(torch, drf):
     a.eps_batched(x, t, c, out=out_a)
     b.eps_batched(x[:2], t[:2], c[:2], out=out_b)
     torch.cuda.synchronize()
-    assert torch.equal(out_b, out_a[:2])
+
+    def same_slots(small, big):
+        # a 2-slot pass and the first slots of a 128-slot pass: the same values up to the order of the GEMMs' k-sums
+        # (tile shapes, and the split of K across workgroups for few-tile problems, depend on the number of rows)
+        return float((small - big).abs().max() / big.abs().max()) < 5e-3
+
+    assert same_slots(out_b, out_a[:2])
+    first = out_b.clone()
     # other stream after a synchronisation: allowed
     with torch.cuda.stream(side):
         b.eps_batched(x[:2], t[:2], c[:2], out=out_b)
     torch.cuda.synchronize()
-    assert torch.equal(out_b, out_a[:2])
+    assert torch.equal(out_b, first)                 # the same call again: bit for bit
     # the same handle on another stream while its own work is still running: refused as well
     a.eps_batched(x, t, c, out=out_a)
     moved = False
