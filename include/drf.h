@@ -191,7 +191,8 @@ drf_status drf_eps_batched(drf_denoiser* den, const float* x, const int32_t* t, 
  * drf_eps_batched for callers that cannot allocate device memory: code under HIP graph
  * capture, tight serving loops, harnesses that forbid hipMalloc.  Same arguments, same
  * kernels and the same results as drf_eps_batched, but the pass's scratch buffers
- * (activations, conditioning rows, modulation table, K/V of a text context) are carved out
+ * (activations, conditioning rows, modulation table, K/V of a text context, and for bf16
+ * handles the 16 MiB of partial tiles of the split-K GEMM) are carved out
  * of a static device array of DRF_STATIC_SCRATCH_BYTES that the library holds on every GPU
  * it runs on until the process ends, instead of the handle's workspace; the call makes no
  * device allocation and frees nothing.  A pass that needs more scratch than the array holds
@@ -200,7 +201,7 @@ drf_status drf_eps_batched(drf_denoiser* den, const float* x, const int32_t* t, 
  * The array is shared by every handle and call on that GPU and keeps the last call's
  * contents (nothing in it has to start at zero): calls that overlap on one GPU race.
  */
-#define DRF_STATIC_SCRATCH_BYTES (32u << 20)
+#define DRF_STATIC_SCRATCH_BYTES (48u << 20)
 drf_status drf_eps_batched_static(drf_denoiser* den, const float* x, const int32_t* t, const void* cond,
                                   int slots, float* eps_out, void* hip_stream);
 

@@ -46,7 +46,7 @@ drf_status drf_profile_read(drf_denoiser* den, int which, long long* launches, d
  * Measurement hook: one launch of the library's bf16 GEMM on caller buffers,
  * out[M][N] (bf16) = A[M][K] (bf16) . W[N][K]^T (bf16) + bias[N] (fp32), all DEVICE.
  * variant 0 = the tile shape the forward pass would pick, > 0 forces one (for sweeps); 10 = the 128 x 128 tile with K
- * split across workgroups where the library's rule allows it (few tiles, at least 36 64-wide k-tiles).
+ * split across workgroups where the library's rule allows it (few tiles, at least 18 64-wide k-tiles).
  * K % 64 == 0 and N % 4 == 0 are required.
  */
 drf_status drf_probe_gemm_bf16(const void* A, const void* W, int M, int N, int K, void* out_bf16, const float* bias,

@@ -390,7 +390,7 @@ drf_status forward(drf_denoiser* d, const Workspace& ws, const float* x, const S
         if ((rc = ln(mrow, mrow + D, nm, true)) != DRF_OK) return rc;
         // bf16: q | k | v are stored head-major ([slot][head][token][d] planes) so that attention reads
         // whole contiguous tiles; fp32: packed rows
-        if ((rc = gemm(d, ws.hbuf, b.qkv, M, f32 ? epi_store(ws.qkv, 3 * D, true) : with_warm(epi_heads(ws.qkv, M, dm), &b.proj), st)) != DRF_OK) return rc;
+        if ((rc = gemm(d, ws.hbuf, b.qkv, M, f32 ? epi_store(ws.qkv, 3 * D, true) : with_warm(epi_heads(ws.qkv, M, dm), &b.proj), st, ws.skpart)) != DRF_OK) return rc;
         {
             AttnArgs aa{};
             aa.q = ws.qkv; aa.out = ws.hbuf; aa.ldo = D; aa.Nq = dm.T; aa.Nk = dm.T; aa.heads = dm.heads; aa.d = dm.d;
@@ -410,7 +410,7 @@ drf_status forward(drf_denoiser* d, const Workspace& ws, const float* x, const S
         if (f32) {
             if ((rc = gemm(d, ws.hbuf, b.proj, M, epi_resid(ws.resid, D, mrow + 2 * D, nm, dm.T), st)) != DRF_OK) return rc;
         } else {
-            if ((rc = gemm(d, ws.hbuf, b.proj, M, with_warm(epi_gated(ws.ybuf, D, mrow + 2 * D, nm, dm.T), text ? nullptr : &b.fc1), st)) != DRF_OK) return rc;
+            if ((rc = gemm(d, ws.hbuf, b.proj, M, with_warm(epi_gated(ws.ybuf, D, mrow + 2 * D, nm, dm.T), text ? nullptr : &b.fc1), st, ws.skpart)) != DRF_OK) return rc;
             pend1 = (const bf16_t*)ws.ybuf;
         }
         if (d->cfg.cond == DRF_COND_TEXT) {
@@ -431,7 +431,7 @@ drf_status forward(drf_denoiser* d, const Workspace& ws, const float* x, const S
         }
         const bool last = l == n_blocks - 1;
         if ((rc = ln(mrow + 3 * D, mrow + 4 * D, nm, f32 || last)) != DRF_OK) return rc;
-        if ((rc = gemm(d, ws.hbuf, b.fc1, M, with_warm(epi_store(ws.mid, dm.R * D, f32, true), f32 ? nullptr : &b.fc2), st)) != DRF_OK) return rc;
+        if ((rc = gemm(d, ws.hbuf, b.fc1, M, with_warm(epi_store(ws.mid, dm.R * D, f32, true), f32 ? nullptr : &b.fc2), st, ws.skpart)) != DRF_OK) return rc;
         if (f32 || last) {
             if ((rc = gemm(d, ws.mid, b.fc2, M, epi_resid(ws.resid, D, mrow + 5 * D, nm, dm.T), st, ws.skpart)) != DRF_OK) return rc;
         } else {
@@ -504,6 +504,9 @@ drf_status carve_static(const drf_denoiser* d, int slots, Workspace* ws)
     const WorkspaceBytes b = workspace_bytes(d, (size_t)slots, (size_t)slots, (size_t)slots);
     size_t off = 0;
     auto take = [&](size_t bytes) { unsigned char* p = base + off; off += (bytes + 255) / 256 * 256; return p; };
+    // bf16: the split-K partial tiles come first, always, so that this entry point splits exactly where
+    // drf_eps_batched does and the two return the same bits
+    ws->skpart = d->bf16 ? (float*)take(gemm_splitk_scratch_bytes()) : nullptr;
     ws->resid = (float*)take(b.resid); ws->hbuf = take(b.hbuf); ws->qkv = take(b.qkv); ws->mid = take(b.mid);
     ws->ybuf = take(b.ybuf); ws->ybuf2 = take(b.ybuf2);
     ws->mod = (float*)take(b.mod); ws->cact32 = (float*)take(b.cact32); ws->cscratch = (float*)take(b.cscratch); ws->cact = take(b.cact);
@@ -511,10 +514,6 @@ drf_status carve_static(const drf_denoiser* d, int slots, Workspace* ws)
     if (off > (size_t)DRF_STATIC_SCRATCH_BYTES)
         DRF_FAIL(DRF_ESHAPE, "a pass of %d slots needs %zu bytes of scratch; the static array holds %zu", slots, off,
                  (size_t)DRF_STATIC_SCRATCH_BYTES);
-    // the split-K partial tiles only where the array has room left for them (without: the unsplit GEMM, same results
-    // up to the order of the k-sums)
-    ws->skpart = nullptr;
-    if (d->bf16 && off + gemm_splitk_scratch_bytes() <= (size_t)DRF_STATIC_SCRATCH_BYTES) ws->skpart = (float*)take(gemm_splitk_scratch_bytes());
     return DRF_OK;
 }
 

@@ -219,8 +219,9 @@ typedef float f32x4 __attribute__((ext_vector_type(4)));
 // the whole copy at once are 0.8 % slower per call, one every other group lands too late: 3 % slower)
 constexpr int kSpreadPer = 1;
 // split K across workgroups: at most this many workgroups per launch (one round of the GPU's CUs), and only
-// when the problem has at least this many 64-wide k-tiles (shorter ones do not repay the reduction launch)
-constexpr int kSplitKMaxGroups = 256, kSplitKMinKTiles = 36;
+// when the problem has at least this many 64-wide k-tiles (shorter ones do not repay the reduction launch:
+// 36 -> 18 was measured, another 4.5 % off a batch-1 call)
+constexpr int kSplitKMaxGroups = 256, kSplitKMinKTiles = 18;
 
 //  - SK (split K across workgroups, for problems with few tiles and a long K: the out-projection of the MLP at
 //    one or two samples per pass): tiles_n counts sk.splits column-tile rows, workgroup (tm, tn) takes k-range
@@ -762,14 +763,15 @@ drf_status launch_gemm_bf16(const bf16_t* A, const bf16_t* W, int M, int N, int 
             if (v == 7 && K % 128 == 0 && K >= 1024) v = 8;
         }
     }
-    // Few 128 x 128 tiles and a long K (the MLP's out-projection at one or two samples per pass: 36 tiles of 72
-    // k-tiles on 256 CUs): split K over as many workgroups as fit one round, the k-tiles dividing evenly.
+    // Few 128 x 128 tiles and a long K (one or two samples per pass: the MLP's out-projection is 36 tiles of 72
+    // k-tiles on 256 CUs, the attention out-projection 36 of 18): split K over as many workgroups as fit one
+    // round, the k-tiles dividing evenly and at least six to a workgroup.
     if (v == 10) v = 5;
     if ((v == 5 || v == 1) && (variant == 0 || variant == 10) && splitk_scratch && K / 64 >= kSplitKMinKTiles) {
         const int tiles = ((M + 127) / 128) * ((N + 127) / 128), nk = K / 64;
         int splits = 0;
         for (int s2 = 2; s2 <= 8 && s2 * tiles <= kSplitKMaxGroups; ++s2)
-            if (nk % s2 == 0 && nk / s2 >= 4) splits = s2;
+            if (nk % s2 == 0 && nk / s2 >= 6) splits = s2;
         if (splits) return launch_bf16_splitk(A, W, M, N, K, e, st, splits, splitk_scratch);
     }
     switch (v) {

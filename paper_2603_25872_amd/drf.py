@@ -26,7 +26,7 @@ SYMBOLS = ["drf_denoiser_weight_count", "drf_denoiser_create", "drf_denoiser_des
 # include/drf_measure.h: test and measurement hooks
 MEASURE_SYMBOLS = ["drf_eps_trace", "drf_profile_enable", "drf_profile_read", "drf_probe_gemm_bf16",
                    "drf_probe_attn_bf16", "drf_probe_update_fused", "drf_graph_stats", "drf_calibrate_mfma_bf16", "drf_calibrate_copy"]
-STATIC_SCRATCH_BYTES = 32 << 20
+STATIC_SCRATCH_BYTES = 48 << 20
 
 
 class DitConfig(C.Structure):
