@@ -368,9 +368,6 @@ gemm_bf16_xl_kernel(const bf16_t* __restrict__ A, const bf16_t* __restrict__ W, 
 
     // tiles 0 .. NS-2 are in flight before the loop; tile kt + NS - 1 is requested once tile kt - 1 has been read
     issue(0, 0);
-#pragma unroll
-    for (int t = 1; t < NS - 1; ++t)
-        if (t < nk) issue(t, t);
     // Gated store, all rows of the tile in one slot (the slot length is a multiple of BM): the tile's BN gate
     // values go to LDS behind the stages, once, and the epilogue reads them from there.  Read from global memory
     // in the epilogue they would be loaded per 16 x 16 piece, each load waited for on the spot (and, from the
@@ -380,8 +377,11 @@ gemm_bf16_xl_kernel(const bf16_t* __restrict__ A, const bf16_t* __restrict__ W, 
     if (gate_lds && tid < BN / 4) {
         const int n = n0 + tid * 4;
         const float4 gv = *reinterpret_cast<const float4*>(e.gate + (size_t)fast_div(m0, e.rps_magic, e.rps_shift) * e.gate_ld + (n < N ? n : 0));
-        *reinterpret_cast<float4*>(sgate + tid * 4) = gv;
-    }
+        *reinterpret_cast<float4*>(sgate + tid * 4) = gv;   // (the compiler waits for every load before this write:
+    }                                                       //  the later stages are requested only now)
+#pragma unroll
+    for (int t = 1; t < NS - 1; ++t)
+        if (t < nk) issue(t, t);
     if (NS > 2 && nk >= NS - 1) wait_vmcnt<LPT * (NS - 2)>(); else wait_vmcnt<0>();
     asm volatile("s_waitcnt lgkmcnt(0)\n\ts_barrier" ::: "memory");
     asm volatile("" ::"v"(warm_val));
@@ -710,9 +710,10 @@ drf_status launch_bf16_splitk(const bf16_t* A, const bf16_t* W, int M, int N, in
                               int splits, float* part)
 {
     constexpr int BM = 128, BN = 128, BK = 64;
-    constexpr size_t smem = (size_t)2 * (BM + BN) * BK * sizeof(bf16_t) + BN * sizeof(float);
+    constexpr int NS = 4;
+    constexpr size_t smem = (size_t)NS * (BM + BN) * BK * sizeof(bf16_t) + BN * sizeof(float);
     static bool attr_set = false;
-    auto kern = gemm_bf16_xl_kernel<BM, BN, BK, 2, 2, 2, 1, true>;
+    auto kern = gemm_bf16_xl_kernel<BM, BN, BK, NS, 2, 2, 1, true>;
     if (!attr_set) {
         DRF_HIP(hipFuncSetAttribute(reinterpret_cast<const void*>(kern), hipFuncAttributeMaxDynamicSharedMemorySize, (int)smem));
         attr_set = true;
@@ -778,7 +779,7 @@ drf_status launch_gemm_bf16(const bf16_t* A, const bf16_t* W, int M, int N, int 
     case 2: return launch_bf16_xl<256, 288, 64, 2, 4, 2>(A, W, M, N, K, e, st);
     case 3: return launch_bf16_xl<256, 256, 64, 2, 4, 2>(A, W, M, N, K, e, st);
     case 4: return launch_bf16_xl<128, 288, 64, 2, 2, 2>(A, W, M, N, K, e, st);
-    case 5: return launch_bf16_xl<128, 128, 64, 2, 2, 2>(A, W, M, N, K, e, st);
+    case 5: return launch_bf16_xl<128, 128, 64, 4, 2, 2>(A, W, M, N, K, e, st);
     case 6: return launch_bf16_xl<256, 288, 64, 2, 4, 3>(A, W, M, N, K, e, st);
     case 7: return launch_bf16_xl<128, 144, 64, 4, 4, 1>(A, W, M, N, K, e, st);
     case 8: return launch_bf16_xl<128, 144, 64, 2, 4, 1, 2>(A, W, M, N, K, e, st);
