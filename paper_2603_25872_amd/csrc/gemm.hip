@@ -429,7 +429,7 @@ gemm_bf16_xl_kernel(const bf16_t* __restrict__ A, const bf16_t* __restrict__ W, 
                 if constexpr (g % NI == 0) wait_frags<later, MI>(fw[g % R], fa[(g / NI) & 1]);
                 else wait_frag<later>(fw[g % R]);
                 static_for<0, MI>([&](auto jc) {
-                    constexpr int j = decltype(jc)::value;
+                    constexpr int j = (g & 1) ? MI - 1 - decltype(jc)::value : decltype(jc)::value;   // snake: one operand changes per MFMA
                     acc[g % NI][j] = __builtin_amdgcn_mfma_f32_16x16x32_bf16(__builtin_bit_cast(bf16x8, fw[g % R]),
                                                                              __builtin_bit_cast(bf16x8, fa[(g / NI) & 1][j]),
                                                                              acc[g % NI][j], 0, 0, 0);
