@@ -40,6 +40,30 @@ def calibrate(torch, drf):
     a = torch.empty(1 << 28, dtype=torch.float32, device="cuda").normal_()
     b = torch.empty_like(a)
     out["copy_1GiB_GBps"] = max(drf.calibrate_copy(a, b, 5) for _ in range(2))
+    del a, b
+    # The library's own wide-tile GEMM on the MLP out-projection shape of configuration 3 (16384 x 1152 x 4608),
+    # back-to-back launches, with N(0, 1) x N(0, 0.02) operands and with all-zero operands: the same instruction
+    # stream, so the ratio is what the chip's power management takes for the operands' bit toggling.
+    M, N, K = 16384, 1152, 4608
+
+    def gemm_rate(A, W, iters=20):
+        bias = torch.zeros(N, device="cuda")
+        o = torch.empty((M, N), dtype=torch.bfloat16, device="cuda")
+        for _ in range(3):
+            drf.probe_gemm_bf16(A, W, bias, out=o)
+        e0, e1 = torch.cuda.Event(enable_timing=True), torch.cuda.Event(enable_timing=True)
+        torch.cuda.synchronize()
+        e0.record()
+        for _ in range(iters):
+            drf.probe_gemm_bf16(A, W, bias, out=o)
+        e1.record()
+        torch.cuda.synchronize()
+        return 2.0 * M * N * K * iters / (e0.elapsed_time(e1) * 1e-3) / 1e12
+
+    out["gemm_16384x1152x4608_zero_operands_TFLOPs"] = gemm_rate(torch.zeros((M, K), dtype=torch.bfloat16, device="cuda"),
+                                                                  torch.zeros((N, K), dtype=torch.bfloat16, device="cuda"))
+    out["gemm_16384x1152x4608_random_operands_TFLOPs"] = gemm_rate(
+        torch.randn((M, K), device="cuda").to(torch.bfloat16), (torch.randn((N, K), device="cuda") * 0.02).to(torch.bfloat16))
     return out
 
 
